@@ -1,0 +1,163 @@
+// Stage 1 - Gaussian fit of the prefill hidden states (paper Sec. 3.2 Step 2; Alg. 1, the
+// "mean(h), var(h)" line): per-channel mean and variance over tokens n_s .. L-1.
+//
+// One pass over hidden[L, d], the largest stream of the whole path (d * elem bytes per token),
+// so the kernel is a pure HBM reader: every wave loads 1 KiB contiguous pieces of a row
+// (64 lanes x 16 B), four waves of a workgroup take interleaved rows, eight rows are in flight
+// per lane.  Sums are taken about a pivot row (shifted data) in fp32 per row chunk, chunks are
+// merged in fp64 in a fixed order (Chan et al. pairwise update) -> deterministic output.
+#include "gvote_internal.hpp"
+
+namespace gvote {
+
+namespace {
+
+constexpr int kFitThreads = 256;
+constexpr int kFitUnroll = 8;
+
+template <typename T>
+__global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitTable tab) {
+  constexpr int NV = Vec16<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int chunk = blockIdx.y;
+  int it = 0;
+  while (it + 1 < tab.n_items && chunk >= tab.it[it + 1].chunk0) ++it;
+  const FitItem I = tab.it[it];
+  const int col = (blockIdx.x * 64 + lane) * NV;
+  const bool active = col < tab.d;
+  const int r0 = I.n_skip + (chunk - I.chunk0) * tab.rows_per_chunk;
+  const int r1 = min(I.L, r0 + tab.rows_per_chunk);
+  const T *base = reinterpret_cast<const T *>(I.hidden) + col;
+
+  float pivot[NV], s[NV], ss[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) { pivot[i] = 0.f; s[i] = 0.f; ss[i] = 0.f; }
+  if (active) {
+    Vec16<T>::load(base + (long long)r0 * I.stride, pivot);
+    for (int r = r0 + wave; r < r1; r += 4 * kFitUnroll) {
+      float x[kFitUnroll][NV];
+#pragma unroll
+      for (int u = 0; u < kFitUnroll; ++u) {
+        const int rr = r + 4 * u;
+        if (rr < r1) {
+          Vec16<T>::load(base + (long long)rr * I.stride, x[u]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < NV; ++i) x[u][i] = pivot[i];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kFitUnroll; ++u) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const float dlt = x[u][i] - pivot[i];
+          s[i] += dlt;
+          ss[i] = fmaf(dlt, dlt, ss[i]);
+        }
+      }
+    }
+  }
+  __shared__ float red[3][64][2 * NV];
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) { red[wave - 1][lane][i] = s[i]; red[wave - 1][lane][NV + i] = ss[i]; }
+  }
+  __syncthreads();
+  if (wave == 0 && active) {
+    const float n = (float)(r1 - r0);
+    float *pm = tab.partial + ((size_t)chunk * 2) * tab.d + col;
+    float *pv = pm + tab.d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const float st = s[i] + red[0][lane][i] + red[1][lane][i] + red[2][lane][i];
+      const float sst = ss[i] + red[0][lane][NV + i] + red[1][lane][NV + i] + red[2][lane][NV + i];
+      pm[i] = pivot[i] + st / n;
+      pv[i] = fmaxf(0.f, sst - st * st / n);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void moments_finalize_kernel(const FitTable tab, int ddof, float *mu, float *var,
+                                                               int item0) {
+  const int it = blockIdx.y;
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= tab.d) return;
+  const FitItem I = tab.it[it];
+  double n = 0.0, mean = 0.0, m2 = 0.0;
+  for (int c = 0; c < I.n_chunks; ++c) {
+    const int r0 = I.n_skip + c * tab.rows_per_chunk;
+    const double nb = (double)(min(I.L, r0 + tab.rows_per_chunk) - r0);
+    const float *pm = tab.partial + ((size_t)(I.chunk0 + c) * 2) * tab.d + col;
+    const double mb = (double)pm[0], vb = (double)pm[tab.d];
+    const double nn = n + nb, delta = mb - mean;
+    mean += delta * (nb / nn);
+    m2 += vb + delta * delta * (n * nb / nn);
+    n = nn;
+  }
+  mu[(size_t)(item0 + it) * tab.d + col] = (float)mean;
+  var[(size_t)(item0 + it) * tab.d + col] = (float)(m2 / (n - (double)ddof));
+}
+
+}  // namespace
+
+FitPlan plan_fit(const gvote_shape *sh, const gvote_item *items, int n_items) {
+  // aim at ~4096 workgroups so that every CU holds several; a chunk is at least 64 rows
+  int64_t rows = 0;
+  for (int i = 0; i < n_items; ++i) rows += items[i].L - items[i].n_skip;
+  const int nv = sh->dtype == GVOTE_F32 ? 4 : 8;
+  const int colblocks = ceil_div(sh->d_model, 64 * nv);
+  int64_t rpc = (rows * colblocks + 4095) / 4096;
+  rpc = (rpc + 31) / 32 * 32;
+  if (rpc < 64) rpc = 64;
+  if (rpc > 4096) rpc = 4096;
+  FitPlan p;
+  p.rows_per_chunk = (int)rpc;
+  p.total_chunks = 0;
+  for (int i = 0; i < n_items; ++i) p.total_chunks += ceil_div(items[i].L - items[i].n_skip, rpc);
+  p.ws_bytes = (size_t)p.total_chunks * 2 * sh->d_model * sizeof(float);
+  return p;
+}
+
+gvote_status launch_fit(const gvote_shape *sh, const gvote_item *items, int n_items, int ddof, float *mu, float *var,
+                        void *ws, hipStream_t st) {
+  const FitPlan plan = plan_fit(sh, items, n_items);
+  const int nv = sh->dtype == GVOTE_F32 ? 4 : 8;
+  const int colblocks = ceil_div(sh->d_model, 64 * nv);
+  int chunk_done = 0;
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    FitTable tab;
+    tab.n_items = nb;
+    tab.d = sh->d_model;
+    tab.rows_per_chunk = plan.rows_per_chunk;
+    tab.pad = 0;
+    tab.partial = reinterpret_cast<float *>(ws) + (size_t)chunk_done * 2 * sh->d_model;
+    int c = 0;
+    for (int i = 0; i < nb; ++i) {
+      const gvote_item &g = items[b0 + i];
+      FitItem &f = tab.it[i];
+      f.hidden = g.hidden;
+      f.stride = g.hidden_row_stride;
+      f.L = g.L;
+      f.n_skip = g.n_skip;
+      f.chunk0 = c;
+      f.n_chunks = ceil_div(g.L - g.n_skip, plan.rows_per_chunk);
+      c += f.n_chunks;
+    }
+    if (c > 65535) return GVOTE_ERR_CAPACITY;
+    const dim3 grid(colblocks, c);
+    if (sh->dtype == GVOTE_F32)
+      hipLaunchKernelGGL(moments_partial_kernel<float>, grid, dim3(kFitThreads), 0, st, tab);
+    else
+      hipLaunchKernelGGL(moments_partial_kernel<bf16_t>, grid, dim3(kFitThreads), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(moments_finalize_kernel, dim3(ceil_div(sh->d_model, 256), nb), dim3(256), 0, st, tab, ddof, mu,
+                       var, b0);
+    GVOTE_CHECK_LAUNCH();
+    chunk_done += c;
+  }
+  return GVOTE_OK;
+}
+
+}  // namespace gvote

@@ -1,0 +1,169 @@
+// Shared declarations of the gfx950 GVote library: descriptor tables that travel to the
+// kernels by value (no device-side descriptor memory, so a call never copies or allocates),
+// storage-type helpers, and the per-stage launch plans used both to size the workspace and
+// to launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gvote.h"
+
+namespace gvote {
+
+// Items per launch batch.  Tables are kernel arguments (<= 4 KiB), larger calls are split.
+constexpr int kMaxItems = 32;
+
+typedef unsigned short bf16_t;   // storage only; arithmetic is fp32
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even, the rounding a model's bf16 store applies (inputs here are finite)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// 16-byte vector of the storage type, widened to fp32.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  __device__ __forceinline__ static void load(const float *p, float (&o)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+};
+template <> struct Vec16<bf16_t> {
+  static constexpr int N = 8;
+  __device__ __forceinline__ static void load(const bf16_t *p, float (&o)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
+};
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+inline size_t elem_bytes(int dtype) { return dtype == GVOTE_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------- stage 1: fit
+struct FitItem {
+  const void *hidden;
+  long long stride;     // elements
+  int L, n_skip;
+  int chunk0, n_chunks; // this item's row chunks are chunk0 .. chunk0 + n_chunks - 1
+};
+struct FitTable {
+  int n_items, d, rows_per_chunk, pad;
+  float *partial;       // [total_chunks][2][d]: chunk mean, chunk M2
+  FitItem it[kMaxItems];
+};
+struct FitPlan {
+  int rows_per_chunk;
+  int total_chunks;     // over the whole call
+  size_t ws_bytes;
+};
+FitPlan plan_fit(const gvote_shape *sh, const gvote_item *items, int n_items);
+gvote_status launch_fit(const gvote_shape *sh, const gvote_item *items, int n_items, int ddof, float *mu,
+                        float *var, void *ws, hipStream_t st);
+
+// ---------------------------------------------------------------- stage 2: sample + project + rotate
+struct SampleItem {
+  const void *w_q;
+  const void *b_q;
+  unsigned long long seed, stream_id;
+  int pos0, n_future;
+};
+struct SampleTable {
+  int n_items, d, S, SP;          // SP: samples padded to a multiple of 32
+  int n_out, head_dim, ksplits, kslice;
+  float theta;
+  int item0;                      // index of the batch's first item in the call (output offsets)
+  const float *mu, *var;          // [n_items_call, d]
+  void *h_tilde;                  // ws: [n_items_batch][S][d] storage type
+  void *h_tilde_out;              // optional user copy, call-indexed
+  float *partial;                 // ws: [n_items_batch][ksplits][n_out][SP]
+  void *q_out;                    // [n_items_call][S][n_out]
+  SampleItem it[kMaxItems];
+};
+struct SamplePlan {
+  int SP, ksplits, kslice;
+  size_t h_bytes_per_item, partial_bytes_per_item, ws_bytes;
+};
+SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S);
+gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const float *mu,
+                           const float *var, void *q_out, void *h_tilde_out, void *ws, hipStream_t st);
+gvote_status launch_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, hipStream_t st);
+
+// ---------------------------------------------------------------- stage 3: score + select
+struct ScoreItem {
+  const void *k;
+  long long tok_stride, head_stride;   // elements
+  long long mask_off;                  // first word of this item's rowmask block
+  int L, W;                            // W = words per row
+  int row0;                            // first global row of this item within the batch
+  int pad;
+};
+struct ScoreTable {
+  int n_items, S, n_q_heads, n_kv_heads;
+  int head_dim, mode, rows_per_item, item0;
+  float p, scale;
+  const void *q;                       // [n_items_call][S][H_q][d_k]
+  const int *k_per_row;                // call-indexed or null
+  uint32_t *rowmask;
+  float *row_max, *row_sum;            // call-indexed or null
+  ScoreItem it[kMaxItems];
+};
+struct ScorePlan { size_t ws_bytes; };
+ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
+gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
+                                 float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
+                                 float *row_sum, void *ws, size_t ws_bytes, hipStream_t st);
+
+// ---------------------------------------------------------------- stage 4: union + count + compact
+constexpr int kChunkWords = 64;        // a compaction chunk = 64 mask words = 2048 tokens
+struct UnionItem {
+  const void *k, *v;
+  long long tok_stride, head_stride;
+  long long rowmask_off, union_off;    // first word of the item's blocks
+  int L, W;
+  int n_chunks;                        // chunks per KV head = ceil(W / kChunkWords)
+  int chunk0;                          // global id of (item, head 0, chunk 0)
+};
+struct UnionTable {
+  int n_items, S, n_q_heads, n_kv_heads;
+  int head_dim, item0, total_chunks_call, n_heads_call;
+  const uint32_t *rowmask;
+  uint32_t *union_mask;
+  int *chunk_count;                    // ws [total_chunks_call]
+  long long *chunk_base;               // ws [total_chunks_call + 1]
+  int *head_first;                     // ws [n_heads_call + 1]: first chunk of each (item, head)
+  void *k_out, *v_out;
+  int *idx_out;
+  long long capacity;
+  UnionItem it[kMaxItems];
+};
+struct UnionPlan { int total_chunks; size_t off_base, off_head, ws_bytes; };
+UnionPlan plan_union(const gvote_shape *sh, const gvote_item *items, int n_items);
+gvote_status launch_union_compact(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
+                                  const uint32_t *rowmask, uint32_t *union_mask, int *budget, long long *offsets,
+                                  void *k_out, void *v_out, int *idx_out, long long capacity, int *overflow_flag,
+                                  void *ws, hipStream_t st);
+
+#define GVOTE_CHECK_LAUNCH()                                  \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return GVOTE_ERR_HIP; \
+  } while (0)
+
+}  // namespace gvote

@@ -1,0 +1,335 @@
+// Stage 2 - synthetic future queries (paper Sec. 3.2 Step 3; Alg. 1: the Gaussian draw
+// "H~ ~ N(mu, diag sigma^2)", "AverageCosSin(n_f)" and "Q~ = RoPE(H~ W_q, P)").
+//
+//   sample_hidden   Philox4x32-10 (counter = draw index, so any thread regenerates any element)
+//                   -> Box-Muller -> mu + sigma z, rounded to the storage type.  S*d values per
+//                   item (KBs), so it is generated once instead of once per GEMM workgroup.
+//   project_mfma    bf16: the [S, d] x [d, H_q d_k] product is a skinny GEMM whose cost is the one
+//                   read of W_q; W_q rows are the A operand of v_mfma_f32_32x32x16_bf16 straight
+//                   from global memory (each lane owns 64 contiguous bytes of one row per k-step),
+//                   the sampled states are the B operand from LDS.  Split along k so that even a
+//                   single item fills the chip; partial sums are reduced in a fixed order.
+//   project_generic any storage type, plain FMA (the fp32 configuration).
+//   rope_finalize   k-split reduction + bias + rotation by the averaged cos/sin (computed in fp64
+//                   on the device: the angle pos * omega needs more than fp32 at 128k) + rounding.
+#include "gvote_internal.hpp"
+
+namespace gvote {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ---- Philox4x32-10 (Salmon et al., SC'11): ten rounds, Weyl key schedule
+__device__ __forceinline__ void philox4x32_10(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c[0]), lo0 = M0 * c[0];
+    const uint32_t hi1 = __umulhi(M1, c[2]), lo1 = M1 * c[2];
+    const uint32_t n0 = hi1 ^ c[1] ^ k0, n2 = hi0 ^ c[3] ^ k1;
+    c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
+    k0 += W0; k1 += W1;
+  }
+}
+
+// u = ((x >> 9) + 1/2) 2^-23 is exact in fp32 and lies strictly inside (0, 1)
+__device__ __forceinline__ float u01(uint32_t x) { return ((float)(x >> 9) + 0.5f) * 0x1.0p-23f; }
+
+__device__ __forceinline__ void box_muller(uint32_t xa, uint32_t xb, float &z_even, float &z_odd) {
+  const float r = sqrtf(-2.0f * logf(u01(xa)));
+  float sn, cs;
+  sincospif(2.0f * u01(xb), &sn, &cs);   // angle 2 pi u_b, argument exact
+  z_even = r * cs;
+  z_odd = r * sn;
+}
+
+__global__ __launch_bounds__(256) void philox_u32_kernel(unsigned long long seed, unsigned long long sid, long long n,
+                                                         uint32_t *out) {
+  const long long blk = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (blk * 4 >= n) return;
+  uint32_t c[4] = {(uint32_t)blk, (uint32_t)((unsigned long long)blk >> 32), (uint32_t)sid, (uint32_t)(sid >> 32)};
+  philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (blk * 4 + i < n) out[blk * 4 + i] = c[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void sample_hidden_kernel(const SampleTable tab) {
+  const int it = blockIdx.y;
+  const long long blk = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long e0 = blk * 4;
+  if (e0 >= (long long)tab.S * tab.d) return;
+  const SampleItem I = tab.it[it];
+  uint32_t c[4] = {(uint32_t)blk, (uint32_t)((unsigned long long)blk >> 32), (uint32_t)I.stream_id,
+                   (uint32_t)(I.stream_id >> 32)};
+  philox4x32_10(c, (uint32_t)I.seed, (uint32_t)(I.seed >> 32));
+  float z[4];
+  box_muller(c[0], c[1], z[0], z[1]);
+  box_muller(c[2], c[3], z[2], z[3]);
+  const int j = (int)(e0 % tab.d);   // d % 4 == 0: the four draws stay inside one sample
+  const float4 m = *reinterpret_cast<const float4 *>(tab.mu + (size_t)(tab.item0 + it) * tab.d + j);
+  const float4 v = *reinterpret_cast<const float4 *>(tab.var + (size_t)(tab.item0 + it) * tab.d + j);
+  const float mm[4] = {m.x, m.y, m.z, m.w}, vv[4] = {v.x, v.y, v.z, v.w};
+  T *dst = reinterpret_cast<T *>(tab.h_tilde) + (size_t)it * tab.S * tab.d + e0;
+  T *dst2 = tab.h_tilde_out ? reinterpret_cast<T *>(tab.h_tilde_out) + (size_t)(tab.item0 + it) * tab.S * tab.d + e0
+                            : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const T hv = from_f32<T>(fmaf(sqrtf(vv[i]), z[i], mm[i]));
+    dst[i] = hv;
+    if (dst2) dst2[i] = hv;
+  }
+}
+
+// ---- bf16 MFMA projection.  grid (ceil(n_out/128), ksplits, items), 256 threads.
+template <int NSB>
+__global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t *Bs = reinterpret_cast<bf16_t *>(smem);   // [32*NSB][kslice + 8]
+  const int it = blockIdx.z, ks = blockIdx.y;
+  const int k0 = ks * tab.kslice;
+  const int klen = min(tab.kslice, tab.d - k0);
+  const int ldb = tab.kslice + 8;
+  const bf16_t *hsrc = reinterpret_cast<const bf16_t *>(tab.h_tilde) + (size_t)it * tab.S * tab.d + k0;
+  const int vec_per_row = tab.kslice / 8;
+  for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += 256) {
+    const int s = v / vec_per_row, kk = (v % vec_per_row) * 8;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (s < tab.S && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
+    *reinterpret_cast<uint4 *>(Bs + s * ldb + kk) = val;
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int o = blockIdx.x * 128 + wave * 32 + col;
+  const bool o_ok = o < tab.n_out;
+  const bf16_t *wrow =
+      reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)(o_ok ? o : 0) * tab.d + k0 + hf * 32;
+  floatx16 acc[NSB];
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[sb][r] = 0.f;
+
+  // one k-step = 64 channels: lane (row, hf) owns channels hf*32 .. hf*32+31 of its row, consumed
+  // 8 at a time by four MFMAs; the B operand uses the very same channel assignment.
+#pragma unroll 4
+  for (int kk = 0; kk < tab.kslice; kk += 64) {
+    bf16x8 a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kp = kk + hf * 32 + i * 8;
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (o_ok && kp < klen) raw = *reinterpret_cast<const uint4 *>(wrow + kk + i * 8);
+      a[i] = __builtin_bit_cast(bf16x8, raw);
+    }
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(Bs + (sb * 32 + col) * ldb + kk + hf * 32 + i * 8);
+        acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], __builtin_bit_cast(bf16x8, raw), acc[sb], 0, 0, 0);
+      }
+    }
+  }
+  // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  // Rows are outputs o, columns are samples.
+  float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SP;
+  const int ob = blockIdx.x * 128 + wave * 32;
+#pragma unroll
+  for (int sb = 0; sb < NSB; ++sb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int oo = ob + 8 * (r / 4) + 4 * hf + (r % 4);
+      if (oo < tab.n_out) part[(size_t)oo * tab.SP + sb * 32 + col] = acc[sb][r];
+    }
+  }
+}
+
+// ---- any storage type: one wave per output row, eight samples at a time.  grid (ceil(n_out/4), items)
+template <typename T>
+__global__ __launch_bounds__(256) void project_generic_kernel(const SampleTable tab) {
+  constexpr int NV = Vec16<T>::N;
+  const int it = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int o = blockIdx.x * 4 + wave;
+  if (o >= tab.n_out) return;
+  const T *wrow = reinterpret_cast<const T *>(tab.it[it].w_q) + (size_t)o * tab.d;
+  const T *h = reinterpret_cast<const T *>(tab.h_tilde) + (size_t)it * tab.S * tab.d;
+  float *part = tab.partial + ((size_t)it * tab.n_out + o) * tab.SP;
+  for (int s0 = 0; s0 < tab.SP; s0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = 0.f;
+    for (int j = lane * NV; j < tab.d; j += 64 * NV) {
+      float w[NV];
+      Vec16<T>::load(wrow + j, w);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (s0 + u < tab.S) {
+          float x[NV];
+          Vec16<T>::load(h + (size_t)(s0 + u) * tab.d + j, x);
+#pragma unroll
+          for (int i = 0; i < NV; ++i) acc[u] = fmaf(w[i], x[i], acc[u]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      float a = acc[u];
+      for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+      if (lane == 0) part[s0 + u] = a;
+    }
+  }
+}
+
+// ---- reduction over k-splits, bias, rotation, rounding.  grid (ceil(pairs/8), items), 256 threads
+template <typename T>
+__global__ __launch_bounds__(256) void rope_finalize_kernel(const SampleTable tab) {
+  const int it = blockIdx.y;
+  const SampleItem I = tab.it[it];
+  const int half = tab.head_dim / 2;
+  const int n_pairs = (tab.n_out / tab.head_dim) * half;
+  __shared__ float cs[8][2];
+  if (threadIdx.x < 8) {
+    const int pr = blockIdx.x * 8 + threadIdx.x;
+    if (pr < n_pairs) {
+      const int i = pr % half;
+      const double omega = pow((double)tab.theta, -2.0 * (double)i / (double)tab.head_dim);
+      double c = 0.0, s = 0.0;
+      for (int tau = 0; tau < I.n_future; ++tau) {
+        const double ang = (double)(I.pos0 + tau) * omega;
+        c += cos(ang);
+        s += sin(ang);
+      }
+      cs[threadIdx.x][0] = (float)(c / (double)I.n_future);
+      cs[threadIdx.x][1] = (float)(s / (double)I.n_future);
+    }
+  }
+  __syncthreads();
+  const int slot = threadIdx.x >> 5;
+  const int pair = blockIdx.x * 8 + slot;
+  if (pair >= n_pairs) return;
+  const int hd = pair / half, i = pair % half;
+  const int o1 = hd * tab.head_dim + i, o2 = o1 + half;
+  const float c = cs[slot][0], sn = cs[slot][1];
+  const T *bias = reinterpret_cast<const T *>(I.b_q);
+  const float b1 = bias ? to_f32<T>(bias[o1]) : 0.f, b2 = bias ? to_f32<T>(bias[o2]) : 0.f;
+  T *q = reinterpret_cast<T *>(tab.q_out) + (size_t)(tab.item0 + it) * tab.S * tab.n_out;
+  for (int s = threadIdx.x & 31; s < tab.S; s += 32) {
+    float a = 0.f, b = 0.f;
+    for (int ks = 0; ks < tab.ksplits; ++ks) {
+      const float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SP;
+      a += part[(size_t)o1 * tab.SP + s];
+      b += part[(size_t)o2 * tab.SP + s];
+    }
+    a += b1;
+    b += b2;
+    q[(size_t)s * tab.n_out + o1] = from_f32<T>(a * c - b * sn);
+    q[(size_t)s * tab.n_out + o2] = from_f32<T>(b * c + a * sn);
+  }
+}
+
+bool use_mfma(const gvote_shape *sh, int S) { return sh->dtype == GVOTE_BF16 && S <= 128; }
+
+}  // namespace
+
+SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S) {
+  SamplePlan p;
+  p.SP = (S + 31) / 32 * 32;
+  if (use_mfma(sh, S)) {
+    // k-slices of 512 channels (a multiple of the 64-channel MFMA step); the last may be shorter
+    p.kslice = sh->d_model < 512 ? (sh->d_model + 63) / 64 * 64 : 512;
+    p.ksplits = (sh->d_model + p.kslice - 1) / p.kslice;
+  } else {
+    p.kslice = sh->d_model;
+    p.ksplits = 1;
+  }
+  const int nb = n_items < kMaxItems ? n_items : kMaxItems;
+  const size_t n_out = (size_t)sh->n_q_heads * sh->head_dim;
+  p.h_bytes_per_item = align_up((size_t)S * sh->d_model * elem_bytes(sh->dtype), 256);
+  p.partial_bytes_per_item = (size_t)p.ksplits * n_out * p.SP * sizeof(float);
+  p.ws_bytes = nb * (p.h_bytes_per_item + p.partial_bytes_per_item);
+  return p;
+}
+
+gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const float *mu,
+                           const float *var, void *q_out, void *h_tilde_out, void *ws, hipStream_t st) {
+  const SamplePlan plan = plan_sample(sh, n_items, S);
+  const int n_out = sh->n_q_heads * sh->head_dim;
+  const bool mfma = use_mfma(sh, S);
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    SampleTable tab;
+    tab.n_items = nb; tab.d = sh->d_model; tab.S = S; tab.SP = plan.SP;
+    tab.n_out = n_out; tab.head_dim = sh->head_dim; tab.ksplits = plan.ksplits; tab.kslice = plan.kslice;
+    tab.theta = sh->rope_theta; tab.item0 = b0;
+    tab.mu = mu; tab.var = var;
+    tab.h_tilde = ws;
+    tab.h_tilde_out = h_tilde_out;
+    tab.partial = reinterpret_cast<float *>(reinterpret_cast<char *>(ws) +
+                                            (size_t)(n_items < kMaxItems ? n_items : kMaxItems) * plan.h_bytes_per_item);
+    tab.q_out = q_out;
+    for (int i = 0; i < nb; ++i) {
+      const gvote_item &g = items[b0 + i];
+      SampleItem &s = tab.it[i];
+      s.w_q = g.w_q; s.b_q = g.b_q; s.seed = g.seed; s.stream_id = g.stream_id;
+      s.pos0 = g.pos0; s.n_future = g.n_future;
+    }
+    // the h~ rows of one item are S*d elements apart in the workspace (dense), see sample_hidden_kernel
+    const dim3 gs(ceil_div((int64_t)S * sh->d_model / 4, 256), nb);
+    if (sh->dtype == GVOTE_F32)
+      hipLaunchKernelGGL(sample_hidden_kernel<float>, gs, dim3(256), 0, st, tab);
+    else
+      hipLaunchKernelGGL(sample_hidden_kernel<bf16_t>, gs, dim3(256), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+    if (mfma) {
+      const dim3 gp(ceil_div(n_out, 128), plan.ksplits, nb);
+      const int nsb = plan.SP / 32;
+      const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t);
+      if (nsb == 3)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (nsb == 4)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (nsb == 1)
+        hipLaunchKernelGGL(project_mfma_kernel<1>, gp, dim3(256), lds, st, tab);
+      else if (nsb == 2)
+        hipLaunchKernelGGL(project_mfma_kernel<2>, gp, dim3(256), lds, st, tab);
+      else if (nsb == 3)
+        hipLaunchKernelGGL(project_mfma_kernel<3>, gp, dim3(256), lds, st, tab);
+      else
+        hipLaunchKernelGGL(project_mfma_kernel<4>, gp, dim3(256), lds, st, tab);
+    } else {
+      const dim3 gp(ceil_div(n_out, 4), nb);
+      if (sh->dtype == GVOTE_F32)
+        hipLaunchKernelGGL(project_generic_kernel<float>, gp, dim3(256), 0, st, tab);
+      else
+        hipLaunchKernelGGL(project_generic_kernel<bf16_t>, gp, dim3(256), 0, st, tab);
+    }
+    GVOTE_CHECK_LAUNCH();
+    const dim3 gf(ceil_div((n_out / sh->head_dim) * (sh->head_dim / 2), 8), nb);
+    if (sh->dtype == GVOTE_F32)
+      hipLaunchKernelGGL(rope_finalize_kernel<float>, gf, dim3(256), 0, st, tab);
+    else
+      hipLaunchKernelGGL(rope_finalize_kernel<bf16_t>, gf, dim3(256), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+  }
+  return GVOTE_OK;
+}
+
+gvote_status launch_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, hipStream_t st) {
+  if (n == 0) return GVOTE_OK;
+  const int64_t blocks = (n + 3) / 4;
+  hipLaunchKernelGGL(philox_u32_kernel, dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, st,
+                     (unsigned long long)seed, (unsigned long long)stream_id, (long long)n, out);
+  GVOTE_CHECK_LAUNCH();
+  return GVOTE_OK;
+}
+
+}  // namespace gvote

@@ -1,0 +1,243 @@
+// Stage 3 - scores and per-query selection (paper Eq. (1): logits Q~ K^T / sqrt(d_k) and their
+// softmax; Sec. 3.1: a query's required keys are the smallest set whose attention mass reaches
+// p; Alg. 1's row-wise TopK on logits is the same search with unit weights).
+//
+// select_row_kernel: the exact, general selector.  One workgroup owns one query row (s, h) and
+// recomputes its logits from K in every pass, so nothing of size S*H_q*L is ever stored.
+//   pass 0      m = max_t l_t
+//   pass 1..4   most-significant-digit-first radix search, 8 bits per pass, over the
+//               order-preserving 32-bit image of the fp32 logit.  Each pass histograms the
+//               WEIGHT exp(l - m) (or 1 for TopK) of the keys that still match the digits found
+//               so far; walking the 256 bins from the top finds the digit where the cumulative
+//               weight crosses p*Z (or k).  After four passes the threshold logit tau is known
+//               exactly, with the weight strictly above it and the number of keys equal to it.
+//   pass 5      emit bits: l > tau, plus the first n ties in position order, n the least count
+//               that reaches the target (ties are broken towards the lower position).
+// The logit of a key is computed by the same instruction sequence in every pass, so passes agree
+// bit for bit.
+#include "gvote_internal.hpp"
+
+namespace gvote {
+
+namespace {
+
+constexpr int kSelThreads = 256;
+
+// fp32 -> uint32 that sorts like the float
+__device__ __forceinline__ uint32_t ordered_bits(float f) {
+  const uint32_t b = __float_as_uint(f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(uint32_t u) {
+  return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTable tab) {
+  constexpr int NV = Vec16<T>::N;
+  const int grow = blockIdx.x;
+  const int it = grow / tab.rows_per_item;
+  const int r = grow - it * tab.rows_per_item;
+  const int s = r / tab.n_q_heads, h = r - s * tab.n_q_heads;
+  const int kvh = h / (tab.n_q_heads / tab.n_kv_heads);
+  const ScoreItem I = tab.it[it];
+  const int dk = tab.head_dim;
+  const int L = I.L;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool topk = tab.mode == GVOTE_SELECT_TOPK;
+
+  __shared__ float q_s[256];
+  __shared__ float hist[256];
+  __shared__ int cnt[256];
+  __shared__ float red_f[4];
+  __shared__ int red_i[4];
+  __shared__ uint32_t sh_prefix;
+  __shared__ double sh_above, sh_target, sh_z;
+  __shared__ int sh_ties, sh_take, sh_tie_base;
+
+  const T *qrow = reinterpret_cast<const T *>(tab.q) + ((size_t)(tab.item0 + it) * tab.rows_per_item + r) * dk;
+  if (tid < dk) q_s[tid] = to_f32<T>(qrow[tid]);
+  if (tid == 0) { sh_prefix = 0u; sh_above = 0.0; }
+  __syncthreads();
+
+  const T *kbase = reinterpret_cast<const T *>(I.k) + (long long)kvh * I.head_stride;
+  const float scale = tab.scale;
+  auto logit = [&](int t) -> float {
+    const T *kp = kbase + (long long)t * I.tok_stride;
+    float acc = 0.f;
+    for (int c = 0; c < dk; c += NV) {
+      float kv[NV];
+      Vec16<T>::load(kp + c, kv);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) acc = fmaf(q_s[c + i], kv[i], acc);
+    }
+    return acc * scale + 0.0f;   // "+ 0" turns -0 into +0 so equal logits have one bit pattern
+  };
+
+  // ---- pass 0: row maximum
+  float m = -INFINITY;
+  for (int t = tid; t < L; t += kSelThreads) m = fmaxf(m, logit(t));
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  if (lane == 0) red_f[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
+  __syncthreads();
+
+  const bool keep_all = !topk && tab.p >= 1.0f;
+  const int n_pass = keep_all ? 1 : 4;
+
+  // ---- passes 1..4: weighted radix search for the threshold
+  for (int pass = 0; pass < n_pass; ++pass) {
+    const int shift = 24 - 8 * pass;
+    hist[tid] = 0.f;
+    cnt[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    for (int t = tid; t < L; t += kSelThreads) {
+      const float l = logit(t);
+      const uint32_t u = ordered_bits(l);
+      if (pass == 0 || (u >> (shift + 8)) == prefix) {
+        const float w = topk ? 1.0f : expf(l - m);
+        const int dg = (u >> shift) & 255;
+        atomicAdd(&hist[dg], w);
+        atomicAdd(&cnt[dg], 1);
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      if (pass == 0) {
+        double z = 0.0;
+        for (int dg = 255; dg >= 0; --dg) z += (double)hist[dg];
+        sh_z = z;
+        double target;
+        if (topk) {
+          int k = tab.k_per_row[(size_t)(tab.item0 + it) * tab.rows_per_item + r];
+          k = k < 1 ? 1 : (k > L ? L : k);
+          target = (double)k;
+        } else {
+          target = (double)tab.p * z;
+        }
+        sh_target = target;
+      }
+      const double target = sh_target;
+      double cum = sh_above;
+      int pick = -1, lowest = 0;
+      double cum_lowest = cum;
+      for (int dg = 255; dg >= 0; --dg) {
+        if (cnt[dg] == 0) continue;
+        if (cum + (double)hist[dg] >= target) { pick = dg; break; }
+        lowest = dg;
+        cum_lowest = cum;
+        cum += (double)hist[dg];
+      }
+      if (pick < 0) { pick = lowest; cum = cum_lowest; }   // rounding left the total a hair below the target
+      sh_prefix = (prefix << 8) | (uint32_t)pick;
+      sh_above = cum;
+      sh_ties = cnt[pick];
+    }
+    __syncthreads();
+  }
+
+  uint32_t tau = 0u;
+  int take = 0, ties = 0;
+  if (!keep_all) {
+    if (tid == 0) {
+      const float w_tau = topk ? 1.0f : expf(from_ordered_bits(sh_prefix) - m);
+      const double need = sh_target - sh_above;
+      int n = (int)ceil(need / (double)w_tau);
+      n = n < 1 ? 1 : (n > sh_ties ? sh_ties : n);
+      sh_take = n;
+      sh_tie_base = 0;
+    }
+    __syncthreads();
+    tau = sh_prefix;
+    take = sh_take;
+    ties = sh_ties;
+  }
+  if (tid == 0) {
+    const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
+    if (tab.row_max) tab.row_max[gr] = m;
+    if (tab.row_sum) tab.row_sum[gr] = (float)sh_z;
+  }
+
+  // ---- pass 5: emit the row's bit mask, 256 keys per step, in position order
+  uint32_t *mrow = tab.rowmask + I.mask_off + (long long)r * I.W;
+  const int n_steps = (I.W * 32 + kSelThreads - 1) / kSelThreads;
+  const bool rank_ties = !keep_all && take < ties;
+  for (int step = 0; step < n_steps; ++step) {
+    const int t = step * kSelThreads + tid;
+    bool sel = false, tie = false;
+    if (t < L) {
+      if (keep_all) {
+        sel = true;
+      } else {
+        const uint32_t u = ordered_bits(logit(t));
+        sel = u > tau;
+        tie = u == tau;
+      }
+    }
+    if (tie) {
+      if (!rank_ties) {
+        sel = true;
+      }
+    }
+    if (rank_ties) {
+      // position-ordered rank of this tie among all ties of the row
+      const unsigned long long bal = __ballot(tie);
+      const int before = __popcll(bal & ((1ull << lane) - 1ull));
+      if (lane == 0) red_i[wave] = __popcll(bal);
+      __syncthreads();
+      int base = sh_tie_base;
+      for (int w = 0; w < wave; ++w) base += red_i[w];
+      if (tie && base + before < take) sel = true;
+      __syncthreads();
+      if (tid == 0) sh_tie_base += red_i[0] + red_i[1] + red_i[2] + red_i[3];
+    }
+    const unsigned long long bits = __ballot(sel);
+    const int w0 = (step * kSelThreads + wave * 64) >> 5;
+    if (lane == 0) {
+      if (w0 < I.W) mrow[w0] = (uint32_t)bits;
+      if (w0 + 1 < I.W) mrow[w0 + 1] = (uint32_t)(bits >> 32);
+    }
+    if (rank_ties) __syncthreads();
+  }
+}
+
+}  // namespace
+
+ScorePlan plan_score(const gvote_shape *, const gvote_item *, int, int) {
+  ScorePlan p;
+  p.ws_bytes = 0;
+  return p;
+}
+
+gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
+                                 float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
+                                 float *row_sum, void *ws, size_t ws_bytes, hipStream_t st) {
+  (void)ws; (void)ws_bytes;
+  long long mask_off = 0;
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    ScoreTable tab;
+    tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
+    tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = b0;
+    tab.p = p; tab.scale = (float)(1.0 / sqrt((double)sh->head_dim));
+    tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
+    for (int i = 0; i < nb; ++i) {
+      const gvote_item &g = items[b0 + i];
+      ScoreItem &c = tab.it[i];
+      c.k = g.k; c.tok_stride = g.kv_tok_stride; c.head_stride = g.kv_head_stride;
+      c.L = g.L; c.W = (g.L + 31) / 32; c.mask_off = mask_off; c.row0 = i * tab.rows_per_item; c.pad = 0;
+      mask_off += (long long)tab.rows_per_item * c.W;
+    }
+    const dim3 grid(nb * tab.rows_per_item);
+    if (sh->dtype == GVOTE_F32)
+      hipLaunchKernelGGL(select_row_kernel<float>, grid, dim3(kSelThreads), 0, st, tab);
+    else
+      hipLaunchKernelGGL(select_row_kernel<bf16_t>, grid, dim3(kSelThreads), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+  }
+  return GVOTE_OK;
+}
+
+}  // namespace gvote

@@ -1,0 +1,125 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any launch (no GPU needed, no compute)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2509_03136_amd as g
+    if not os.path.exists(g.lib_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return g
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gvote.h")).read()
+    return sorted(set(re.findall(r"GVOTE_API[^;(]*?\b(gvote_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(g):
+    names = declared_symbols()
+    assert {"gvote_fit_gaussian", "gvote_sample_queries", "gvote_score_select", "gvote_union_compact",
+            "gvote_workspace_bytes", "gvote_status_string", "gvote_abi_version", "gvote_philox_u32"} <= set(names)
+    lib = C.CDLL(g.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+    assert g.abi_version() == 1000
+    for code in range(7):
+        assert g.status_string(code)
+
+
+def test_struct_layout_matches_header(g):
+    assert C.sizeof(g.Shape) == 24
+    assert C.sizeof(g.Item) == 96
+    assert g.Item.L.offset == 64 and g.Item.seed.offset == 80
+
+
+def _shape(g, **kw):
+    base = dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, dtype=g.F32, rope_theta=1e4)
+    base.update(kw)
+    return g.Shape(**base)
+
+
+def _items(g, n=1, **kw):
+    arr = (g.Item * n)()
+    for i in range(n):
+        it = arr[i]
+        it.hidden, it.hidden_row_stride = 0x1000, 256
+        it.w_q, it.b_q, it.k, it.v = 0x2000, None, 0x3000, 0x4000
+        it.kv_tok_stride, it.kv_head_stride = 128, 64
+        it.L, it.n_skip, it.pos0, it.n_future = 512, 4, 512, 1
+        it.seed, it.stream_id = 1, i
+        for k, v in kw.items():
+            setattr(it, k, v)
+    return arr
+
+
+def test_workspace_size_is_host_logic(g):
+    L = g.lib()
+    sh, it = _shape(g), _items(g, 3)
+    n = L.gvote_workspace_bytes(C.byref(sh), it, 3, 8)
+    assert n > 0 and n % 256 == 0
+    assert L.gvote_workspace_bytes(C.byref(sh), it, 0, 8) == 0
+    assert L.gvote_workspace_bytes(C.byref(sh), it, 3, 0) == 0
+    assert L.gvote_workspace_bytes(C.byref(_shape(g, n_q_heads=3)), it, 3, 8) == 0
+    assert L.gvote_workspace_bytes(None, it, 3, 8) == 0
+    big = _items(g, 3, L=1 << 20)
+    assert L.gvote_workspace_bytes(C.byref(sh), big, 3, 8) > n
+
+
+def test_bad_arguments_are_rejected_before_any_launch(g):
+    L = g.lib()
+    sh, it = _shape(g), _items(g)
+    ws, wsn = 0x10000, 1 << 30
+    INVALID, SHAPE, UNSUP, WS, CAP = 1, 2, 3, 4, 5
+    fit = L.gvote_fit_gaussian
+    assert fit(None, it, 1, 1, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), None, 1, 1, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), it, 0, 1, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), it, 1, 2, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), it, 1, 1, None, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), it, 1, 1, 0x100, 0x200, ws, 16, None) == WS
+    assert fit(C.byref(sh), _items(g, L=1), 1, 1, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), _items(g, n_skip=511), 1, 1, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert fit(C.byref(sh), _items(g, hidden=0x1004), 1, 1, 0x100, 0x200, ws, wsn, None) == SHAPE
+    assert fit(C.byref(sh), _items(g, hidden_row_stride=250), 1, 1, 0x100, 0x200, ws, wsn, None) == SHAPE
+    assert fit(C.byref(_shape(g, dtype=7)), it, 1, 1, 0x100, 0x200, ws, wsn, None) == UNSUP
+    assert fit(C.byref(_shape(g, n_q_heads=3)), it, 1, 1, 0x100, 0x200, ws, wsn, None) == SHAPE
+    assert fit(C.byref(_shape(g, head_dim=512)), it, 1, 1, 0x100, 0x200, ws, wsn, None) == UNSUP
+    smp = L.gvote_sample_queries
+    assert smp(C.byref(sh), it, 1, 0, 0x100, 0x200, 0x300, None, ws, wsn, None) == INVALID
+    assert smp(C.byref(sh), it, 1, 129, 0x100, 0x200, 0x300, None, ws, wsn, None) == CAP
+    assert smp(C.byref(sh), _items(g, w_q=None), 1, 8, 0x100, 0x200, 0x300, None, ws, wsn, None) == INVALID
+    assert smp(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, None, ws, 8, None) == WS
+    sel = L.gvote_score_select
+    assert sel(C.byref(sh), it, 1, 8, 0x100, 0.0, 0, None, 0x200, None, None, ws, wsn, None) == INVALID
+    assert sel(C.byref(sh), it, 1, 8, 0x100, 1.5, 0, None, 0x200, None, None, ws, wsn, None) == INVALID
+    assert sel(C.byref(sh), it, 1, 8, 0x100, 0.9, 1, None, 0x200, None, None, ws, wsn, None) == INVALID
+    assert sel(C.byref(sh), it, 1, 8, 0x100, 0.9, 5, None, 0x200, None, None, ws, wsn, None) == INVALID
+    assert sel(C.byref(sh), it, 1, 8, None, 0.9, 0, None, 0x200, None, None, ws, wsn, None) == INVALID
+    assert sel(C.byref(sh), _items(g, kv_head_stride=60), 1, 8, 0x100, 0.9, 0, None, 0x200, None, None, ws, wsn,
+               None) == SHAPE
+    uni = L.gvote_union_compact
+    assert uni(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, 0x400, 0x500, 0x600, None, 10, None, ws, wsn,
+               None) == INVALID
+    assert uni(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, 0x400, 0x500, 0x600, None, -1, 0x700, ws, wsn,
+               None) == INVALID
+    assert uni(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, 0x400, 0x500, 0x600, None, 10, 0x700, ws, 8,
+               None) == WS
+    assert L.gvote_philox_u32(1, 2, -1, None, None) == INVALID
+    assert L.gvote_philox_u32(1, 2, 0, None, None) == 0
+
+
+def test_missing_library_is_a_loud_error(g, monkeypatch, tmp_path):
+    import paper_2509_03136_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_HERE", str(tmp_path))
+    with pytest.raises(ImportError):
+        b.lib()
