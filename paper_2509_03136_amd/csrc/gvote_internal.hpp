@@ -53,6 +53,11 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
 
+// Accumulator of a dot product over stored values: fp32 for bf16 storage (products of bf16 are exact
+// in fp32), fp64 for fp32 storage so that the fp32 configuration keeps its 1e-5 agreement.
+template <typename T> struct Acc { typedef float type; };
+template <> struct Acc<float> { typedef double type; };
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 inline size_t elem_bytes(int dtype) { return dtype == GVOTE_F32 ? 4 : 2; }
@@ -118,7 +123,8 @@ struct ScoreItem {
 struct ScoreTable {
   int n_items, S, n_q_heads, n_kv_heads;
   int head_dim, mode, rows_per_item, item0;
-  float p, scale;
+  float p, pad2;
+  double scale;                        // 1 / sqrt(head_dim)
   const void *q;                       // [n_items_call][S][H_q][d_k]
   const int *k_per_row;                // call-indexed or null
   uint32_t *rowmask;

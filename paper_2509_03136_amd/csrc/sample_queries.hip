@@ -162,9 +162,9 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const SampleTable 
   const T *h = reinterpret_cast<const T *>(tab.h_tilde) + (size_t)it * tab.S * tab.d;
   float *part = tab.partial + ((size_t)it * tab.n_out + o) * tab.SP;
   for (int s0 = 0; s0 < tab.SP; s0 += 8) {
-    float acc[8];
+    typename Acc<T>::type acc[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] = 0.f;
+    for (int u = 0; u < 8; ++u) acc[u] = 0;
     for (int j = lane * NV; j < tab.d; j += 64 * NV) {
       float w[NV];
       Vec16<T>::load(wrow + j, w);
@@ -174,15 +174,16 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const SampleTable 
           float x[NV];
           Vec16<T>::load(h + (size_t)(s0 + u) * tab.d + j, x);
 #pragma unroll
-          for (int i = 0; i < NV; ++i) acc[u] = fmaf(w[i], x[i], acc[u]);
+          for (int i = 0; i < NV; ++i)
+            acc[u] = fma((typename Acc<T>::type)w[i], (typename Acc<T>::type)x[i], acc[u]);
         }
       }
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      float a = acc[u];
+      typename Acc<T>::type a = acc[u];
       for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
-      if (lane == 0) part[s0 + u] = a;
+      if (lane == 0) part[s0 + u] = (float)a;
     }
   }
 }

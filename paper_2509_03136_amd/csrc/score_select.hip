@@ -61,17 +61,18 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
   __syncthreads();
 
   const T *kbase = reinterpret_cast<const T *>(I.k) + (long long)kvh * I.head_stride;
-  const float scale = tab.scale;
+  typedef typename Acc<T>::type acc_t;
+  const acc_t scale = (acc_t)tab.scale;
   auto logit = [&](int t) -> float {
     const T *kp = kbase + (long long)t * I.tok_stride;
-    float acc = 0.f;
+    acc_t acc = 0;
     for (int c = 0; c < dk; c += NV) {
       float kv[NV];
       Vec16<T>::load(kp + c, kv);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) acc = fmaf(q_s[c + i], kv[i], acc);
+      for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[c + i], (acc_t)kv[i], acc);
     }
-    return acc * scale + 0.0f;   // "+ 0" turns -0 into +0 so equal logits have one bit pattern
+    return (float)(acc * scale) + 0.0f;   // "+ 0" turns -0 into +0 so equal logits have one bit pattern
   };
 
   // ---- pass 0: row maximum
@@ -221,7 +222,7 @@ gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items,
     ScoreTable tab;
     tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
     tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = b0;
-    tab.p = p; tab.scale = (float)(1.0 / sqrt((double)sh->head_dim));
+    tab.p = p; tab.scale = 1.0 / sqrt((double)sh->head_dim);
     tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     for (int i = 0; i < nb; ++i) {
       const gvote_item &g = items[b0 + i];
