@@ -107,6 +107,9 @@ def main():
     stage_ms = {name: sum(ev[k][j].elapsed_time(ev[k][j + 1]) for k in range(args.steps)) / args.steps
                 for j, (name, _) in enumerate(stages)}
 
+    pipe.select()
+    torch.cuda.synchronize()
+    fallback_rows = pipe.fallback_rows() if wl.dtype == "bf16" else None
     tok = sum(wl.lengths)
     budget = pipe.budget.cpu().numpy()
     kept = int(pipe.offsets[-1].item())
@@ -133,6 +136,7 @@ def main():
         "stage_ms": stage_ms,
         "stage_algorithmic_GBs": {k: ab[k] / (stage_ms[k] * 1e-3) / 1e9 for k in stage_ms},
         "kept_fraction": rho,
+        "select_fallback_rows": fallback_rows,
         "budget_per_item": [int(x) for x in budget.sum(axis=1)],
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,

@@ -142,7 +142,10 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * `mode` (TOPP uses p in (0, 1]; p >= 1 keeps every key; TOPK uses k_per_row[n_items * S * n_q_heads],
  * device int32, clamped to [1, L]; pass NULL for TOPP).  Ties are broken towards the lower position.
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
- * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip. */
+ * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
+ * Diagnostic: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
+ * of ws holds, after the call, the number of rows that had to be redone by the exact general selector
+ * (cut outside the histogram window, or too many keys tied around the cut). */
 GVOTE_API gvote_status gvote_score_select(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
                                 int32_t S, const void *q, float p, int32_t mode, const int32_t *k_per_row,
                                 uint32_t *rowmask, float *row_max, float *row_sum,

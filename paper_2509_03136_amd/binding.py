@@ -214,6 +214,10 @@ class Pipeline:
         score_select(self.b, self.S, self.q, self.p, self.rowmask, row_max=self.row_max, row_sum=self.row_sum,
                      ws=self.ws)
 
+    def fallback_rows(self) -> int:
+        """Rows of the last select() redone by the exact general selector (matrix-core path only)."""
+        return int(self.ws[:4].view(torch.int32).item())
+
     def compact(self):
         union_compact(self.b, self.S, self.rowmask, self.union_mask, self.budget, self.offsets, self.k_out,
                       self.v_out, self.idx_out, self.capacity, self.overflow, self.ws)

@@ -58,6 +58,55 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return
 template <typename T> struct Acc { typedef float type; };
 template <> struct Acc<float> { typedef double type; };
 
+// One step of the weighted most-significant-digit-first search, run by ONE wave (all 64 lanes):
+// walking the 256 digit bins from 255 down, find the first non-empty digit at which `above` plus
+// the weights met so far reaches `target`; if rounding leaves the total short, take the lowest
+// non-empty digit.  Returns the digit; `above` becomes the weight strictly above it.
+__device__ __forceinline__ int pick_digit_wave(const float *hist, const int *cnt, double &above, double target,
+                                               int lane) {
+  // lane 0 holds digits 255..252, lane 63 digits 3..0
+  double h[4];
+  int c[4];
+  double mine = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int dg = 255 - (lane * 4 + i);
+    h[i] = (double)hist[dg];
+    c[i] = cnt[dg];
+    mine += h[i];
+  }
+  double x = mine;
+  for (int off = 1; off < 64; off <<= 1) {
+    const double y = __shfl_up(x, off, 64);
+    if (lane >= off) x += y;
+  }
+  double cum = above + (x - mine);   // weight above this lane's first digit
+  int pick = -1, low = -1;
+  double cum_pick = 0.0, cum_low = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int dg = 255 - (lane * 4 + i);
+    if (c[i] != 0) {
+      if (pick < 0 && cum + h[i] >= target) { pick = dg; cum_pick = cum; }
+      low = dg;
+      cum_low = cum;
+    }
+    cum += h[i];
+  }
+  const unsigned long long hit = __ballot(pick >= 0);
+  int src;
+  if (hit) {
+    src = __ffsll((long long)hit) - 1;
+  } else {
+    const unsigned long long any = __ballot(low >= 0);
+    src = 63 - __clzll((long long)any);
+    pick = low;
+    cum_pick = cum_low;
+  }
+  above = __shfl(cum_pick, src, 64);
+  return __shfl(pick, src, 64);
+}
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 inline size_t elem_bytes(int dtype) { return dtype == GVOTE_F32 ? 4 : 2; }
@@ -129,9 +178,60 @@ struct ScoreTable {
   const int *k_per_row;                // call-indexed or null
   uint32_t *rowmask;
   float *row_max, *row_sum;            // call-indexed or null
+  const int *flags;                    // null, or one int per batch row (stride flag_stride): 0 = skip the row
+  int flag_stride, pad3;
+  int *n_fallback;                     // null, or counter incremented once per row this kernel processes
   ScoreItem it[kMaxItems];
 };
 struct ScorePlan { size_t ws_bytes; };
+
+// bf16 fast path (score_fast.hip)
+constexpr int kBins = 256;            // histogram bins per row below the row maximum
+constexpr int kBinsPerUnit = 16;      // bins per unit of logit: bin width 1/16, window 16 units
+constexpr int kCandCap = 1024;        // boundary-bin candidates a row may collect before it is redone exactly
+struct RowInfo {
+  float mdot;       // row maximum of the raw dot product
+  int astar;        // absolute bin index floor(dot * c1) in which the cut falls
+  int flag;         // 1: redo this row with the general selector
+  int pad;
+  double above;     // weight of all keys in bins above astar (relative to exp(-max))
+  double target;    // p * Z
+};
+struct FastItem {
+  const void *k;
+  long long tok_stride, head_stride;
+  long long mask_off;
+  int L, W;
+  int n_chunks;     // key chunks per KV head
+  int wg0;          // first workgroup of the item
+  int part0;        // first (head, chunk) slot of the item in the partial arrays
+  int pad;
+};
+struct FastTable {
+  int n_items, S, Hq, Hkv, G, NQ, NQB, chunk_keys;
+  int item0, rows_per_item;
+  float scale, c1, c2, p;   // c1 = bins per raw-dot unit, c2 = log2(e) / sqrt(d_k)
+  const void *q;
+  uint32_t *rowmask;
+  float *row_max, *row_sum;
+  float *part_max;          // [slot][NQ]
+  float *part_hist;         // [slot][NQ][kBins]
+  RowInfo *info;            // [rows of the batch]
+  int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
+  int *cand_cnt;            // [rows]
+  uint2 *cands;             // [rows][kCandCap]: (raw dot bits, position)
+  FastItem it[kMaxItems];
+};
+struct FastPlan { size_t off_max, off_hist, off_info, off_cnt, off_cands, ws_bytes; };
+bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
+FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
+gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
+                               float p, uint32_t *rowmask, float *row_max, float *row_sum, void *ws, hipStream_t st);
+// the exact general selector on a batch of <= kMaxItems items; with `flags` only rows whose flag is set
+gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
+                                        const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
+                                        long long mask_off0, float *row_max, float *row_sum, const int *flags,
+                                        int flag_stride, int *n_fallback, hipStream_t st);
 ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                  float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,

@@ -36,6 +36,7 @@ template <typename T>
 __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTable tab) {
   constexpr int NV = Vec16<T>::N;
   const int grow = blockIdx.x;
+  if (tab.flags && tab.flags[(size_t)grow * tab.flag_stride] == 0) return;
   const int it = grow / tab.rows_per_item;
   const int r = grow - it * tab.rows_per_item;
   const int s = r / tab.n_q_heads, h = r - s * tab.n_q_heads;
@@ -57,7 +58,11 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
 
   const T *qrow = reinterpret_cast<const T *>(tab.q) + ((size_t)(tab.item0 + it) * tab.rows_per_item + r) * dk;
   if (tid < dk) q_s[tid] = to_f32<T>(qrow[tid]);
-  if (tid == 0) { sh_prefix = 0u; sh_above = 0.0; }
+  if (tid == 0) {
+    sh_prefix = 0u;
+    sh_above = 0.0;
+    if (tab.n_fallback) atomicAdd(tab.n_fallback, 1);
+  }
   __syncthreads();
 
   const T *kbase = reinterpret_cast<const T *>(I.k) + (long long)kvh * I.head_stride;
@@ -105,36 +110,29 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
       }
     }
     __syncthreads();
-    if (tid == 0) {
-      if (pass == 0) {
-        double z = 0.0;
-        for (int dg = 255; dg >= 0; --dg) z += (double)hist[dg];
-        sh_z = z;
-        double target;
-        if (topk) {
-          int k = tab.k_per_row[(size_t)(tab.item0 + it) * tab.rows_per_item + r];
-          k = k < 1 ? 1 : (k > L ? L : k);
-          target = (double)k;
-        } else {
-          target = (double)tab.p * z;
-        }
-        sh_target = target;
+    if (pass == 0 && tid == 0) {
+      double z = 0.0;
+      for (int dg = 255; dg >= 0; --dg) z += (double)hist[dg];
+      sh_z = z;
+      double target;
+      if (topk) {
+        int k = tab.k_per_row[(size_t)(tab.item0 + it) * tab.rows_per_item + r];
+        k = k < 1 ? 1 : (k > L ? L : k);
+        target = (double)k;
+      } else {
+        target = (double)tab.p * z;
       }
-      const double target = sh_target;
-      double cum = sh_above;
-      int pick = -1, lowest = 0;
-      double cum_lowest = cum;
-      for (int dg = 255; dg >= 0; --dg) {
-        if (cnt[dg] == 0) continue;
-        if (cum + (double)hist[dg] >= target) { pick = dg; break; }
-        lowest = dg;
-        cum_lowest = cum;
-        cum += (double)hist[dg];
+      sh_target = target;
+    }
+    if (pass == 0) __syncthreads();
+    if (wave == 0) {
+      double above = sh_above;
+      const int pick = pick_digit_wave(hist, cnt, above, sh_target, lane);
+      if (lane == 0) {
+        sh_prefix = (prefix << 8) | (uint32_t)pick;
+        sh_above = above;
+        sh_ties = cnt[pick];
       }
-      if (pick < 0) { pick = lowest; cum = cum_lowest; }   // rounding left the total a hair below the target
-      sh_prefix = (prefix << 8) | (uint32_t)pick;
-      sh_above = cum;
-      sh_ties = cnt[pick];
     }
     __syncthreads();
   }
@@ -206,37 +204,52 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
 
 }  // namespace
 
-ScorePlan plan_score(const gvote_shape *, const gvote_item *, int, int) {
+ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S) {
   ScorePlan p;
-  p.ws_bytes = 0;
+  p.ws_bytes = fast_path_ok(sh, S, GVOTE_SELECT_TOPP, 0.5f) ? plan_fast(sh, items, n_items, S).ws_bytes : 0;
   return p;
+}
+
+gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
+                                        const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
+                                        long long mask_off0, float *row_max, float *row_sum, const int *flags,
+                                        int flag_stride, int *n_fallback, hipStream_t st) {
+  ScoreTable tab;
+  tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
+  tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = item0;
+  tab.p = p; tab.pad2 = 0.f; tab.scale = 1.0 / sqrt((double)sh->head_dim);
+  tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
+  tab.flags = flags; tab.flag_stride = flag_stride; tab.pad3 = 0; tab.n_fallback = n_fallback;
+  long long mask_off = mask_off0;
+  for (int i = 0; i < nb; ++i) {
+    const gvote_item &g = items[i];
+    ScoreItem &c = tab.it[i];
+    c.k = g.k; c.tok_stride = g.kv_tok_stride; c.head_stride = g.kv_head_stride;
+    c.L = g.L; c.W = (g.L + 31) / 32; c.mask_off = mask_off; c.row0 = i * tab.rows_per_item; c.pad = 0;
+    mask_off += (long long)tab.rows_per_item * c.W;
+  }
+  const dim3 grid(nb * tab.rows_per_item);
+  if (sh->dtype == GVOTE_F32)
+    hipLaunchKernelGGL(select_row_kernel<float>, grid, dim3(kSelThreads), 0, st, tab);
+  else
+    hipLaunchKernelGGL(select_row_kernel<bf16_t>, grid, dim3(kSelThreads), 0, st, tab);
+  GVOTE_CHECK_LAUNCH();
+  return GVOTE_OK;
 }
 
 gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                  float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
                                  float *row_sum, void *ws, size_t ws_bytes, hipStream_t st) {
-  (void)ws; (void)ws_bytes;
+  (void)ws_bytes;
+  if (fast_path_ok(sh, S, mode, p))
+    return launch_score_fast(sh, items, n_items, S, q, p, rowmask, row_max, row_sum, ws, st);
   long long mask_off = 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
-    ScoreTable tab;
-    tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
-    tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = b0;
-    tab.p = p; tab.scale = 1.0 / sqrt((double)sh->head_dim);
-    tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
-    for (int i = 0; i < nb; ++i) {
-      const gvote_item &g = items[b0 + i];
-      ScoreItem &c = tab.it[i];
-      c.k = g.k; c.tok_stride = g.kv_tok_stride; c.head_stride = g.kv_head_stride;
-      c.L = g.L; c.W = (g.L + 31) / 32; c.mask_off = mask_off; c.row0 = i * tab.rows_per_item; c.pad = 0;
-      mask_off += (long long)tab.rows_per_item * c.W;
-    }
-    const dim3 grid(nb * tab.rows_per_item);
-    if (sh->dtype == GVOTE_F32)
-      hipLaunchKernelGGL(select_row_kernel<float>, grid, dim3(kSelThreads), 0, st, tab);
-    else
-      hipLaunchKernelGGL(select_row_kernel<bf16_t>, grid, dim3(kSelThreads), 0, st, tab);
-    GVOTE_CHECK_LAUNCH();
+    const gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, mode, k_per_row, rowmask,
+                                                        mask_off, row_max, row_sum, nullptr, 0, nullptr, st);
+    if (stt != GVOTE_OK) return stt;
+    for (int i = 0; i < nb; ++i) mask_off += (long long)S * sh->n_q_heads * ((items[b0 + i].L + 31) / 32);
   }
   return GVOTE_OK;
 }

@@ -235,6 +235,36 @@ def test_select_degenerate_cases(g):
     assert np.array_equal(gm, r2["rowmask"])
 
 
+def test_select_bf16_fallbacks_and_ties(g):
+    """bf16 (matrix-core path): cases the histogram cannot settle must fall back to the exact selector."""
+    wl = W.scaled(W.config(2), lengths=(1500,), S=4)
+    it = W.make_items(wl, "cpu")[0]
+    ref = U.oracle_item(wl, it)
+    q = ref["q_tilde"][None]
+    stol = U.STAGE_TOL["bf16"]
+    # the cut lies far below the maximum (p -> 1): beyond the histogram window
+    for p in (0.999999, 0.9999999):
+        gm, _ = _select_case(g, wl, [it], q, p)
+        nb = U.check_rowmask_sandwich(gm, ref["logits"], U.p32(p), min(stol, (1 - U.p32(p)) / 4))
+        say("  p", p, "boundary", nb, "mean row size", gm.sum(-1).mean())
+    # all keys equal: every key lands in one bin, candidate lists overflow; ties -> lowest positions
+    it0 = dict(it, k=torch.zeros_like(it["k"]))
+    gm, _ = _select_case(g, wl, [it0], q, 0.9)
+    want = O.top_p_select(np.zeros(1500), U.p32(0.9))
+    assert np.all(gm == want[None, None, :])
+    # every key duplicated: exact ties inside the boundary bin are resolved towards the lower position
+    kd = it["k"].clone()
+    kd[1::2] = kd[0::2]
+    lg = O.scores(ref["q_tilde"], U.f32np(kd))
+    for p in (0.5, 0.95):
+        gm, _ = _select_case(g, wl, [dict(it, k=kd)], q, p)
+        assert U.check_rowmask_sandwich(gm, lg, U.p32(p), stol) <= 8
+    # a tiny p: only the arg-max key of each row
+    gm, _ = _select_case(g, wl, [it], q, 1e-6)
+    assert np.all(gm.sum(-1) == 1)
+    assert np.array_equal(gm.argmax(-1), ref["logits"].argmax(-1))
+
+
 def test_select_topk_mode(g):
     wl = W.scaled(W.config(2), lengths=(700,), S=4)
     it = W.make_items(wl, "cpu")[0]
