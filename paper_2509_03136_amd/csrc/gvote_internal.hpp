@@ -215,7 +215,7 @@ struct FastTable {
   uint32_t *rowmask;
   float *row_max, *row_sum;
   float *part_max;          // [slot][NQ]
-  float *part_hist;         // [slot][NQ][kBins]
+  uint32_t *part_hist;      // [slot][NQ][kBins]: fixed-point bin weights; last bin: a float's bits
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
   int *cand_cnt;            // [rows]

@@ -34,6 +34,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte lane of a K row
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
@@ -48,6 +49,16 @@ __device__ __forceinline__ uint32_t ordered_bits(float f) {
 __device__ __forceinline__ float from_ordered_bits(uint32_t u) {
   return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
 }
+
+// Fixed-point histogram bins (integer LDS atomics run ~30x faster than float ones on this chip).
+// Bins live on an absolute grid of the raw dot product d: a = floor(d * c1), 16 bins per unit of
+// logit.  A key adds exp((l - E_a)) * 2^kFixBits to its bin, E_a the bin's UPPER edge, so every term
+// lies in (0.94, 1] * 2^18 whatever the row maximum is, and a chunk of <= 8192 keys cannot overflow
+// 32 bits.  Bin j of a row is absolute bin top - j (top = bin of the row maximum); everything deeper
+// than kBins - 1 bins is clamped into the last bin, measured against that bin's edge (such keys weigh
+// < 1.2e-7 of the maximum each; below 2^-19 of the edge they round to nothing).
+constexpr int kFixBits = 18;
+constexpr float kLog2ePerBin = 1.44269504088896340736f / (float)kBinsPerUnit;   // log2 weight per bin
 
 // position of accumulator register r of lane (hf = lane / 32) inside the 32-key tile
 __device__ __forceinline__ int key_of(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
@@ -101,42 +112,105 @@ struct Tile {
     }
   }
 
-  // coalesced fetch of keys t0 .. t0+31 of one KV head (zeros beyond L)
-  __device__ __forceinline__ void fetch(uint4 (&pre)[LOADS], const bf16_t *khead, long long tok_stride, int t0, int L,
+  // coalesced fetch of keys t0 .. t0+31 of one KV head.  No branches (the compiler then counts the
+  // outstanding loads exactly and the two-tile prefetch really overlaps): positions at or beyond `end`
+  // re-read key end-1, their products are discarded by the caller's validity test.
+  __device__ __forceinline__ void fetch(u32x4 (&pre)[LOADS], const bf16_t *khead, long long tok_stride, int t0, int end,
                                         int lane) const {
     const int piece = lane % PPR, sub = lane / PPR;
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
-      const int t = t0 + j * RPL + sub;
-      pre[j] = make_uint4(0, 0, 0, 0);
-      if (t < L) pre[j] = *reinterpret_cast<const uint4 *>(khead + (long long)t * tok_stride + piece * 8);
+      const int t = min(t0 + j * RPL + sub, end - 1);
+      pre[j] = *reinterpret_cast<const u32x4 *>(khead + (long long)t * tok_stride + piece * 8);
     }
   }
 
-  __device__ __forceinline__ void stage(const uint4 (&pre)[LOADS], unsigned char *lds, int lane) const {
+  __device__ __forceinline__ void stage(const u32x4 (&pre)[LOADS], unsigned char *lds, int lane) const {
     const int piece = lane % PPR, sub = lane / PPR;
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
       const int key = j * RPL + sub;
       const int phys = piece ^ (key & (PPR - 1));
-      *reinterpret_cast<uint4 *>(lds + (key * PPR + phys) * 16) = pre[j];
+      *reinterpret_cast<u32x4 *>(lds + (key * PPR + phys) * 16) = pre[j];
     }
   }
 
-  __device__ __forceinline__ void compute(floatx16 (&acc)[2], const unsigned char *lds, int lane, bool two) const {
+  // all eight A operands are read before the first MFMA so the LDS latency is paid once per tile
+  template <bool TWO>
+  __device__ __forceinline__ void compute(floatx16 (&acc)[2], const unsigned char *lds, int lane) const {
     const int key = lane & 31, hf = lane >> 5;
+    bf16x8 a[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int phys = (2 * ks + hf) ^ (key & (PPR - 1));
+      a[ks] = *reinterpret_cast<const bf16x8 *>(lds + (key * PPR + phys) * 16);
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int phys = (2 * ks + hf) ^ (key & (PPR - 1));
-      const uint4 raw = *reinterpret_cast<const uint4 *>(lds + (key * PPR + phys) * 16);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[0][ks], acc[0], 0, 0, 0);
-      if (two) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[1][ks], acc[1], 0, 0, 0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[0][ks], acc[0], 0, 0, 0);
+      if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[1][ks], acc[1], 0, 0, 0);
     }
   }
 };
+
+// The K stream of one wave: tiles wave, wave + 8, wave + 16, ... of the chunk [t_begin, t_end), with the
+// global loads of the next TWO tiles in flight (registers) while the current one is multiplied: with
+// 8 waves per CU that keeps 128 KiB per CU outstanding, what HBM latency needs at full bandwidth.
+// `epi(acc, t0)` consumes a tile's 32 x 64 products; `round_end(round)` runs after every kRoundTiles
+// tiles of every wave (all waves call it equally often, so it may hold workgroup barriers).
+template <int DK, bool TWO, class Epi, class RoundEnd>
+__device__ __forceinline__ void stream_tiles_impl(const Tile<DK> &T, unsigned char *lds, const bf16_t *khead,
+                                                  long long tok_stride, int t_begin, int t_end, int wave, int lane,
+                                                  Epi &&epi, RoundEnd &&round_end) {
+  constexpr int LOADS = Tile<DK>::LOADS;
+  const int n_tiles = (t_end - t_begin + 31) >> 5;
+  const int n_rounds = (n_tiles + kWaves * kRoundTiles - 1) / (kWaves * kRoundTiles);
+  u32x4 pa[LOADS], pb[LOADS];
+  // (positions are clamped inside fetch, so the first two fetches need no guard)
+  T.fetch(pa, khead, tok_stride, t_begin + wave * 32, t_end, lane);
+  T.fetch(pb, khead, tok_stride, t_begin + (wave + kWaves) * 32, t_end, lane);
+  for (int k = 0; k < n_rounds * kRoundTiles; k += 2) {
+    {
+      const int tile = wave + kWaves * k;
+      if (tile < n_tiles) {
+        const int t0 = t_begin + tile * 32;
+        T.stage(pa, lds, lane);
+        if (tile + 2 * kWaves < n_tiles) T.fetch(pa, khead, tok_stride, t0 + 2 * kWaves * 32, t_end, lane);
+        __builtin_amdgcn_wave_barrier();
+        floatx16 acc[2];
+        T.template compute<TWO>(acc, lds, lane);
+        __builtin_amdgcn_wave_barrier();
+        epi(acc, t0, k);
+      }
+    }
+    {
+      const int tile = wave + kWaves * (k + 1);
+      if (tile < n_tiles) {
+        const int t0 = t_begin + tile * 32;
+        T.stage(pb, lds, lane);
+        if (tile + 2 * kWaves < n_tiles) T.fetch(pb, khead, tok_stride, t0 + 2 * kWaves * 32, t_end, lane);
+        __builtin_amdgcn_wave_barrier();
+        floatx16 acc[2];
+        T.template compute<TWO>(acc, lds, lane);
+        __builtin_amdgcn_wave_barrier();
+        epi(acc, t0, k + 1);
+      }
+    }
+    if ((k + 2) % kRoundTiles == 0) round_end((k + 2) / kRoundTiles - 1);
+  }
+}
+
+template <int DK, class Epi, class RoundEnd>
+__device__ __forceinline__ void stream_tiles(const Tile<DK> &T, unsigned char *lds, const bf16_t *khead,
+                                             long long tok_stride, int t_begin, int t_end, int wave, int lane,
+                                             bool two, Epi &&epi, RoundEnd &&round_end) {
+  if (two)
+    stream_tiles_impl<DK, true>(T, lds, khead, tok_stride, t_begin, t_end, wave, lane, epi, round_end);
+  else
+    stream_tiles_impl<DK, false>(T, lds, khead, tok_stride, t_begin, t_end, wave, lane, epi, round_end);
+}
 
 // ------------------------------------------------------------------ pass A: chunk maxima
 template <int DK>
@@ -145,35 +219,28 @@ __global__ __launch_bounds__(kThreads) void score_max_kernel(const FastTable tab
   __shared__ uint32_t smax[64];
   const WgCoord c = decode_wg(tab, blockIdx.x);
   const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
   if (tid < 64) smax[tid] = 0u;
   Tile<DK> T;
   T.load_q(tab, c.it, c.kvh, c.n0, lane);
   const bool two = c.n0 + 32 < tab.NQ;
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
-  const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
   float mx[2] = {-INFINITY, -INFINITY};
-  uint4 pre[Tile<DK>::LOADS];
-  if (wave < n_tiles) T.fetch(pre, khead, I.tok_stride, c.t_begin + wave * 32, c.t_end, lane);
   __syncthreads();
-  for (int tile = wave; tile < n_tiles; tile += kWaves) {
-    const int t0 = c.t_begin + tile * 32;
-    T.stage(pre, tiles[wave], lane);
-    if (tile + kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + kWaves * 32, c.t_end, lane);
-    __builtin_amdgcn_wave_barrier();
-    floatx16 acc[2];
-    T.compute(acc, tiles[wave], lane, two);
-    __builtin_amdgcn_wave_barrier();
-    if (t0 + 32 <= c.t_end) {
+  stream_tiles<DK>(
+      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
+      [&](const floatx16(&acc)[2], int t0, int) __attribute__((always_inline)) {
+        if (t0 + 32 <= c.t_end) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
-    } else {
+          for (int r = 0; r < 16; ++r) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
+        } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (t0 + key_of(r, hf) < c.t_end) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
-      }
-    }
-  }
+          for (int r = 0; r < 16; ++r) {
+            if (t0 + key_of(r, hf) < c.t_end) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
+          }
+        }
+      },
+      [](int) {});
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
     float v = fmaxf(mx[nb], __shfl_xor(mx[nb], 32, 64));
@@ -188,96 +255,64 @@ __global__ __launch_bounds__(kThreads) void score_max_kernel(const FastTable tab
 template <int DK>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
-  __shared__ float hist[64 * (kBins + 1)];
-  __shared__ float s_ref[64];
+  __shared__ uint32_t hist[64 * (kBins + 1)];
   __shared__ int s_top[64];
   const WgCoord c = decode_wg(tab, blockIdx.x);
   const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, col = lane & 31;
-  for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0.f;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, col = lane & 31;
+  for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0u;
   if (tid < 64) {
     float m = -INFINITY;
     if (c.n0 + tid < tab.NQ) {
       const float *pm = tab.part_max + (size_t)(I.part0 + c.kvh * I.n_chunks) * tab.NQ + c.n0 + tid;
       for (int ch = 0; ch < I.n_chunks; ++ch) m = fmaxf(m, pm[(size_t)ch * tab.NQ]);
     }
-    s_ref[tid] = m * tab.c2;
     s_top[tid] = (int)floorf(m * tab.c1);
   }
   Tile<DK> T;
   T.load_q(tab, c.it, c.kvh, c.n0, lane);
   const bool two = c.n0 + 32 < tab.NQ;
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
-  const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
-  uint4 pre[Tile<DK>::LOADS];
-  if (wave < n_tiles) T.fetch(pre, khead, I.tok_stride, c.t_begin + wave * 32, c.t_end, lane);
   __syncthreads();
   const int nblk = two ? 2 : 1;
-  float ref[2];
   int top[2];
-  float *hrow[2];
+  uint32_t *hrow[2];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    ref[nb] = s_ref[32 * nb + col];
     top[nb] = s_top[32 * nb + col];
     hrow[nb] = hist + (32 * nb + col) * (kBins + 1);
   }
   const float c1 = tab.c1, c2 = tab.c2;
-  // raw dot below which a key falls into the collecting (last) bin: those are summed in a register
-  float dtail[2], tail[2] = {0.f, 0.f};
+  // x = d * c2 - (a + 1) * kLog2ePerBin + kFixBits is log2 of the fixed-point term of a key in bin a
+  const float ebias = (float)kFixBits - kLog2ePerBin;
+  float atail[2];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    const bool ok = c.n0 + 32 * nb + col < tab.NQ;
-    dtail[nb] = ok ? ((float)(top[nb] - (kBins - 2)) - 0.5f) / c1 : INFINITY;
-    if (!ok) ref[nb] = INFINITY;     // weight exp2(-inf) = 0 for rows that do not exist
+    if (c.n0 + 32 * nb + col >= tab.NQ) top[nb] = 1 << 24;   // rows that do not exist: always the last bin, weight 0
+    atail[nb] = (float)(top[nb] - (kBins - 1));
   }
-  auto hist_add = [&](float d, int nb) {
-    const float w = __builtin_amdgcn_exp2f(fmaf(d, c2, -ref[nb]));
-    // floor(d * c1) is the authority on the bin; the register shortcut is only taken when the key is
-    // surely at or beyond the last bin (d < dtail - margin), anything near the edge goes the exact way
-    if (d < dtail[nb]) {
-      tail[nb] += w;
-    } else {
-      const int a = (int)floorf(d * c1);
-      const int j = min(top[nb] - a, kBins - 1);
-      atomicAdd(hrow[nb] + j, w);
-    }
-  };
-  for (int tile = wave; tile < n_tiles; tile += kWaves) {
-    const int t0 = c.t_begin + tile * 32;
-    T.stage(pre, tiles[wave], lane);
-    if (tile + kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + kWaves * 32, c.t_end, lane);
-    __builtin_amdgcn_wave_barrier();
-    floatx16 acc[2];
-    T.compute(acc, tiles[wave], lane, two);
-    __builtin_amdgcn_wave_barrier();
-    if (t0 + 32 <= c.t_end) {
+  stream_tiles<DK>(
+      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
+      [&](const floatx16(&acc)[2], int t0, int) __attribute__((always_inline)) {
+        const bool full = t0 + 32 <= c.t_end;
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        if (nb < nblk) {
+        for (int nb = 0; nb < 2; ++nb) {
+          if (nb < nblk) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) hist_add(acc[nb][r], nb);
+            for (int r = 0; r < 16; ++r) {
+              const float d = acc[nb][r];
+              const float af = fmaxf(floorf(d * c1), atail[nb]);
+              const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
+              uint32_t u = (uint32_t)(__builtin_amdgcn_exp2f(x) + 0.5f);
+              if (!full) u = t0 + key_of(r, hf) < c.t_end ? u : 0u;
+              atomicAdd(hrow[nb] + (top[nb] - (int)af), u);
+            }
+          }
         }
-      }
-    } else {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        if (nb < nblk) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (t0 + key_of(r, hf) < c.t_end) hist_add(acc[nb][r], nb);
-        }
-      }
-    }
-  }
-  // the collecting bin was kept in registers; lanes of rows that do not exist hold zeros
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const float v = tail[nb] + __shfl_xor(tail[nb], 32, 64);
-    if (lane < 32 && c.n0 + 32 * nb + col < tab.NQ) atomicAdd(hrow[nb] + (kBins - 1), v);
-  }
+      },
+      [](int) {});
   __syncthreads();
-  float *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
+  uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
   const int rows = min(64, tab.NQ - c.n0);
   for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
 }
@@ -292,12 +327,14 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   const FastItem I = tab.it[it];
   const int j = threadIdx.x, lane = j & 63, wave = j >> 6;
   const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
-  double mine = 0.0;
   float m = -INFINITY;
-  for (int ch = 0; ch < I.n_chunks; ++ch) {
-    mine += (double)tab.part_hist[((slot0 + ch) * tab.NQ + n) * kBins + j];
-    m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
-  }
+  for (int ch = 0; ch < I.n_chunks; ++ch) m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
+  unsigned long long acc = 0ull;
+  for (int ch = 0; ch < I.n_chunks; ++ch) acc += tab.part_hist[((slot0 + ch) * tab.NQ + n) * kBins + j];
+  // weight of bin j relative to exp(max): fixed-point sum * 2^-kFixBits * exp2(edge_j - max), in log2 units
+  const int top = (int)floorf(m * tab.c1);
+  const double edge = (double)(top - j + 1) * (double)kLog2ePerBin;
+  const double mine = ldexp((double)acc, -kFixBits) * exp2(edge - (double)m * (double)tab.c2);
   // inclusive scan over bins (bin 0 = highest logits)
   __shared__ double wsum[4];
   double x = mine;
@@ -339,18 +376,21 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
   __shared__ int ccnt[64];
   __shared__ int cbase[64];
   __shared__ int s_astar[64];
+  __shared__ int s_row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
   const WgCoord c = decode_wg(tab, blockIdx.x);
   const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, col = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, col = lane & 31;
   const int row_base = c.it * tab.rows_per_item;   // batch-local row index of (s = 0, h = 0)
   if (tid < 64) {
     const int n = c.n0 + tid;
-    int a = 0x7FFFFFFF;
+    int a = 0x7FFFFFFF, r = -1;
     if (n < tab.NQ) {
       const int s = n / tab.G, g = n % tab.G;
-      a = tab.info[row_base + s * tab.Hq + c.kvh * tab.G + g].astar;
+      r = s * tab.Hq + c.kvh * tab.G + g;
+      a = tab.info[row_base + r].astar;
     }
     s_astar[tid] = a;
+    s_row[tid] = r;
     ccnt[tid] = 0;
   }
   Tile<DK> T;
@@ -363,105 +403,95 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
   astar[1] = s_astar[32 + col];
   const float c1 = tab.c1;
   const int nblk = two ? 2 : 1;
-  uint4 pre[Tile<DK>::LOADS];
+  constexpr int kRoundWords = kWaves * kRoundTiles;
+  // raw dot below which a key surely lies under the row's cut bin (half a bin of margin; rows that do
+  // not exist carry astar = INT_MAX and never match)
+  float dcut[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) dcut[nb] = astar[nb] == 0x7FFFFFFF ? INFINITY : ((float)astar[nb] - 0.5f) / c1;
 
-  for (int round0 = c.t_begin; round0 < c.t_end; round0 += kRoundKeys) {
-    // tile (wave, j) of the round covers keys round0 + (j * kWaves + wave) * 32 ...
-    int t_next = round0 + wave * 32;
-    if (t_next < c.t_end) T.fetch(pre, khead, I.tok_stride, t_next, c.t_end, lane);
-    for (int jt = 0; jt < kRoundTiles; ++jt) {
-      const int widx = jt * kWaves + wave;
-      const int t0 = round0 + widx * 32;
-      uint32_t bits[2] = {0u, 0u};
-      if (t0 < c.t_end) {
-        T.stage(pre, tiles[wave], lane);
-        t_next = t0 + kWaves * 32;
-        if (jt + 1 < kRoundTiles && t_next < c.t_end) T.fetch(pre, khead, I.tok_stride, t_next, c.t_end, lane);
-        __builtin_amdgcn_wave_barrier();
-        floatx16 acc[2];
-        T.compute(acc, tiles[wave], lane, two);
-        __builtin_amdgcn_wave_barrier();
-        auto classify = [&](float d, int nb, int key) {
-          const int a = (int)floorf(d * c1);
-          if (a > astar[nb]) {
-            bits[nb] |= 1u << key;
-          } else if (a == astar[nb]) {
-            const int nl = 32 * nb + col;
-            const int slot = atomicAdd(&ccnt[nl], 1);
-            if (slot < kLocalCand) cbuf[nl][slot] = make_uint2(__float_as_uint(d), (uint32_t)(t0 + key));
-          }
-        };
-        if (t0 + 32 <= c.t_end) {
+  stream_tiles<DK>(
+      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
+      [&](const floatx16(&acc)[2], int t0, int k) __attribute__((always_inline)) {
+        uint32_t bits[2] = {0u, 0u};
+        const bool full = t0 + 32 <= c.t_end;
+        // most tiles hold no key at or above any row's cut bin: one max per row settles that
+        float mx0 = acc[0][0], mx1 = acc[1][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) { mx0 = fmaxf(mx0, acc[0][r]); mx1 = fmaxf(mx1, acc[1][r]); }
+        const bool near = mx0 >= dcut[0] || mx1 >= dcut[1];
+        if (__any(near)) {
+          uint32_t cmask[2] = {0u, 0u};
 #pragma unroll
           for (int nb = 0; nb < 2; ++nb) {
             if (nb < nblk) {
 #pragma unroll
-              for (int r = 0; r < 16; ++r) classify(acc[nb][r], nb, key_of(r, hf));
+              for (int r = 0; r < 16; ++r) {
+                const int key = key_of(r, hf);
+                const bool valid = full || t0 + key < c.t_end;
+                const int a = (int)floorf(acc[nb][r] * c1);
+                bits[nb] |= (valid && a > astar[nb]) ? (1u << key) : 0u;
+                cmask[nb] |= (valid && a == astar[nb]) ? (1u << r) : 0u;
+              }
             }
           }
-        } else {
+          if (__any((cmask[0] | cmask[1]) != 0u)) {   // keys inside the cut bin: rare
 #pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
-            if (nb < nblk) {
+            for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-              for (int r = 0; r < 16; ++r)
-                if (t0 + key_of(r, hf) < c.t_end) classify(acc[nb][r], nb, key_of(r, hf));
+              for (int r = 0; r < 16; ++r) {
+                if (cmask[nb] & (1u << r)) {
+                  const int nl = 32 * nb + col;
+                  const int slot = atomicAdd(&ccnt[nl], 1);
+                  if (slot < kLocalCand)
+                    cbuf[nl][slot] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
+                }
+              }
             }
           }
         }
-      }
+        const int widx = (k % kRoundTiles) * kWaves + wave;
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const uint32_t w = bits[nb] | __shfl_xor(bits[nb], 32, 64);
-        if (lane < 32) mwords[32 * nb + lane][widx] = w;
-      }
-    }
-    __syncthreads();
-    // mask words of this round: row n, words round0/32 .. ; every row writes one contiguous run
-    {
-      const int w_first = round0 >> 5;
-      const int n_words = min(kWaves * kRoundTiles, ((c.t_end - round0) + 31) >> 5);
-      for (int i = tid; i < 64 * kWaves * kRoundTiles; i += kThreads) {
-        const int nl = i / (kWaves * kRoundTiles), w = i % (kWaves * kRoundTiles);
-        const int n = c.n0 + nl;
-        if (n < tab.NQ && w < n_words) {
-          const int s = n / tab.G, g = n % tab.G;
-          const int r = s * tab.Hq + c.kvh * tab.G + g;
-          tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = mwords[nl][w];
+        for (int nb = 0; nb < 2; ++nb) {
+          const uint32_t w = bits[nb] | __shfl_xor(bits[nb], 32, 64);
+          if (lane < 32) mwords[32 * nb + lane][widx] = w;
         }
-      }
-    }
-    // boundary candidates of this round -> the rows' global lists
-    if (tid < 64) {
-      const int n = c.n0 + tid;
-      int cnt = ccnt[tid];
-      cbase[tid] = -1;
-      if (n < tab.NQ && cnt > 0) {
-        const int s = n / tab.G, g = n % tab.G;
-        const int grow = row_base + s * tab.Hq + c.kvh * tab.G + g;
-        if (cnt > kLocalCand) {
-          tab.info[grow].flag = 1;
-        } else {
-          const int b = atomicAdd(&tab.cand_cnt[grow], cnt);
-          if (b + cnt <= kCandCap) cbase[tid] = b;   // otherwise resolve sees the count and flags the row
+      },
+      [&](int round) __attribute__((always_inline)) {
+        const int round0 = c.t_begin + round * kRoundKeys;
+        __syncthreads();
+        // mask words of this round: every row writes one contiguous run of up to 128 bytes
+        const int w_first = round0 >> 5;
+        const int n_words = min(kRoundWords, ((c.t_end - round0) + 31) >> 5);
+        for (int i = tid; i < 64 * kRoundWords; i += kThreads) {
+          const int nl = i / kRoundWords, w = i % kRoundWords;
+          const int r = s_row[nl];
+          if (r >= 0 && w < n_words) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = mwords[nl][w];
         }
-      }
-    }
-    __syncthreads();
-    for (int i = tid; i < 64 * kLocalCand; i += kThreads) {
-      const int nl = i / kLocalCand, sl = i % kLocalCand;
-      const int b = cbase[nl];
-      if (b >= 0 && sl < ccnt[nl]) {
-        const int n = c.n0 + nl;
-        const int s = n / tab.G, g = n % tab.G;
-        const int grow = row_base + s * tab.Hq + c.kvh * tab.G + g;
-        tab.cands[(size_t)grow * kCandCap + b + sl] = cbuf[nl][sl];
-      }
-    }
-    __syncthreads();
-    if (tid < 64) ccnt[tid] = 0;
-    __syncthreads();
-  }
+        // boundary candidates of this round -> the rows' global lists
+        if (tid < 64) {
+          const int cnt = ccnt[tid];
+          const int r = s_row[tid];
+          cbase[tid] = -1;
+          if (r >= 0 && cnt > 0) {
+            if (cnt > kLocalCand) {
+              tab.info[row_base + r].flag = 1;
+            } else {
+              const int b = atomicAdd(&tab.cand_cnt[row_base + r], cnt);
+              if (b + cnt <= kCandCap) cbase[tid] = b;   // else resolve sees the count and flags the row
+            }
+          }
+        }
+        __syncthreads();
+        for (int i = tid; i < 64 * kLocalCand; i += kThreads) {
+          const int nl = i / kLocalCand, sl = i % kLocalCand;
+          const int b = cbase[nl];
+          if (b >= 0 && sl < ccnt[nl]) tab.cands[(size_t)(row_base + s_row[nl]) * kCandCap + b + sl] = cbuf[nl][sl];
+        }
+        __syncthreads();
+        if (tid < 64) ccnt[tid] = 0;
+        __syncthreads();
+      });
 }
 
 // ------------------------------------------------------------------ per row: exact cut among the candidates
@@ -591,7 +621,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.q = q; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.part_max = reinterpret_cast<float *>(wsb + pl.off_max);
-    tab.part_hist = reinterpret_cast<float *>(wsb + pl.off_hist);
+    tab.part_hist = reinterpret_cast<uint32_t *>(wsb + pl.off_hist);
     tab.info = reinterpret_cast<RowInfo *>(wsb + pl.off_info);
     tab.cand_cnt = reinterpret_cast<int *>(wsb + pl.off_cnt);
     tab.cands = reinterpret_cast<uint2 *>(wsb + pl.off_cands);
