@@ -201,6 +201,7 @@ struct FastItem {
   const void *k;
   long long tok_stride, head_stride;
   long long mask_off;
+  long long tmax0;  // first float of the item's [H_kv][W][NQ] tile maxima
   int L, W;
   int n_chunks;     // key chunks per KV head
   int wg0;          // first workgroup of the item
@@ -214,15 +215,17 @@ struct FastTable {
   const void *q;
   uint32_t *rowmask;
   float *row_max, *row_sum;
-  float *part_max;          // [slot][NQ]
+  float *part_max;          // [slot][NQ]: chunk maximum of the raw dot
+  int *part_top;            // [slot][NQ]: top (absolute bin) of the chunk's histogram window
   uint32_t *part_hist;      // [slot][NQ][kBins]: fixed-point bin weights; last bin: a float's bits
+  float *tile_max;          // per (item, KV head, 32-key tile, row): maximum raw dot, written by pass 1
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
   int *cand_cnt;            // [rows]
   uint2 *cands;             // [rows][kCandCap]: (raw dot bits, position)
   FastItem it[kMaxItems];
 };
-struct FastPlan { size_t off_max, off_hist, off_info, off_cnt, off_cands, ws_bytes; };
+struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, ws_bytes; };
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,

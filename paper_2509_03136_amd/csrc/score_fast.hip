@@ -212,108 +212,198 @@ __device__ __forceinline__ void stream_tiles(const Tile<DK> &T, unsigned char *l
     stream_tiles_impl<DK, false>(T, lds, khead, tok_stride, t_begin, t_end, wave, lane, epi, round_end);
 }
 
-// ------------------------------------------------------------------ pass A: chunk maxima
-template <int DK>
-__global__ __launch_bounds__(kThreads) void score_max_kernel(const FastTable tab) {
-  __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
-  __shared__ uint32_t smax[64];
-  const WgCoord c = decode_wg(tab, blockIdx.x);
-  const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
-  if (tid < 64) smax[tid] = 0u;
+// ------------------------------------------------------------------ pass 1: maxima + weight histograms, one K read
+// The row maximum is not known while the chunk streams by, so the 256-bin window of each row slides:
+// bins sit on the absolute grid a = floor(d * c1) and hold weights relative to their own upper edge,
+// hence raising a window is a plain shift of the LDS row (bins pushed past the end are re-referenced
+// into the last bin).  Waves run free of each other; only when a wave meets a key above a window top
+// (after the first tile: rarely, tops carry two units of headroom) does it call for a workgroup event:
+//   requester: record the new maximum, set `pending`, enter the event;
+//   every wave looks at `pending` before it bins a tile (and while it idles after its last tile), so all
+//   eight waves enter the same event exactly once: barrier - each wave slides the windows of the eight
+//   rows it owns - `pending` cleared - barrier - reload the tops.
+// Inside an event no wave touches the histogram, outside nobody moves it.  A wave that has finished its
+// tiles keeps serving events until all eight have finished (`done`).
+struct HistCtl {
+  int top[64];          // window top (absolute bin) of each row, kTopUnset before the first key
+  uint32_t newmax[64];  // ordered bits of the largest raw dot that asked for a higher window
+  uint32_t rowmax[64];  // ordered bits of the chunk maximum of each row
+  int pending, done, aborted, pad;
+};
+constexpr int kTopUnset = -(1 << 24);
+constexpr int kHeadroom = 2 * kBinsPerUnit;
+
+template <int DK, bool TWO>
+__device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
+                                                unsigned char *ldstile, uint32_t *hist, HistCtl *S) {
+  constexpr int LOADS = Tile<DK>::LOADS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
+            col = lane & 31;
   Tile<DK> T;
   T.load_q(tab, c.it, c.kvh, c.n0, lane);
-  const bool two = c.n0 + 32 < tab.NQ;
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
-  float mx[2] = {-INFINITY, -INFINITY};
-  __syncthreads();
-  stream_tiles<DK>(
-      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
-      [&](const floatx16(&acc)[2], int t0, int) __attribute__((always_inline)) {
-        if (t0 + 32 <= c.t_end) {
+  const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
+  const float c1 = tab.c1, c2 = tab.c2;
+  const float ebias = (float)kFixBits - kLog2ePerBin;
+  uint32_t *hrow[2] = {hist + col * (kBins + 1), hist + (32 + col) * (kBins + 1)};
+  volatile int *pending = &S->pending;
+  volatile int *done = &S->done;
+  int top[2] = {kTopUnset, kTopUnset};      // this lane's copy of its two rows' window tops
+  float mxrun[2] = {-INFINITY, -INFINITY};
+
+  auto sync_event = [&]() __attribute__((always_inline)) {
+    __syncthreads();
+    for (int rr = 0; rr < 8; ++rr) {
+      const int row = 8 * wave + rr;
+      const int amax = (int)floorf(from_ordered_bits(S->newmax[row]) * c1);
+      const int oldtop = S->top[row];
+      if (amax > oldtop) {            // wave-uniform
+        const int newtop = amax + kHeadroom;
+        uint32_t *h = hist + row * (kBins + 1);
+        const long long sh = (long long)newtop - (long long)oldtop;
+        uint32_t v[4];
+        float spill = 0.f;            // weight pushed past the window, re-referenced to the last bin's edge
 #pragma unroll
-          for (int r = 0; r < 16; ++r) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            if (t0 + key_of(r, hf) < c.t_end) { mx[0] = fmaxf(mx[0], acc[0][r]); mx[1] = fmaxf(mx[1], acc[1][r]); }
-          }
+        for (int i = 0; i < 4; ++i) {
+          const int j = lane * 4 + i;
+          v[i] = h[j];
+          const long long jn = j + sh;
+          if (jn >= kBins - 1 && v[i] != 0u)
+            spill += (float)v[i] * __builtin_amdgcn_exp2f(-(float)(jn - (kBins - 1)) * kLog2ePerBin);
         }
-      },
-      [](int) {});
+        for (int off = 32; off > 0; off >>= 1) spill += __shfl_xor(spill, off, 64);
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    float v = fmaxf(mx[nb], __shfl_xor(mx[nb], 32, 64));
-    if (lane < 32) atomicMax(&smax[32 * nb + lane], ordered_bits(v));
+        for (int i = 0; i < 4; ++i) {
+          const int j = lane * 4 + i;       // destination bin
+          const long long src = j - sh;
+          // all lanes take part in the exchange (a lane must be active to be read from)
+          const int si = (int)(src & 3);
+          const uint32_t pick = si == 0 ? v[0] : si == 1 ? v[1] : si == 2 ? v[2] : v[3];
+          const uint32_t got = __shfl(pick, src >= 0 ? (int)(src >> 2) : 0, 64);
+          h[j] = j == kBins - 1 ? (uint32_t)(spill + 0.5f) : (src >= 0 ? got : 0u);
+        }
+        if (lane == 0) S->top[row] = newtop;
+      }
+    }
+    if (tid == 0) *pending = 0;       // between the barriers: nobody can be asking right now
+    __syncthreads();
+    top[0] = S->top[col];
+    top[1] = S->top[32 + col];
+  };
+
+  auto tile_body = [&](u32x4(&pre)[LOADS], int tile) __attribute__((always_inline)) {
+    const int t0 = c.t_begin + tile * 32;
+    floatx16 acc[2];
+    // looked at early so the LDS latency hides behind the MFMAs; an event that opens after this look is
+    // joined at the next tile (its barrier waits for this wave, so the histogram stays put meanwhile)
+    const int pend_seen = *pending;
+    T.stage(pre, ldstile, lane);
+    if (tile + 2 * kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + 2 * kWaves * 32, c.t_end, lane);
+    __builtin_amdgcn_wave_barrier();
+    T.template compute<TWO>(acc, ldstile, lane);
+    __builtin_amdgcn_wave_barrier();
+    // positions beyond the chunk repeat its last key (see fetch), so they cannot raise a maximum
+    float mx0 = acc[0][0], mx1 = acc[1][0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) { mx0 = fmaxf(mx0, acc[0][r]); mx1 = fmaxf(mx1, acc[1][r]); }
+    mx0 = fmaxf(mx0, __shfl_xor(mx0, 32, 64));
+    mx1 = fmaxf(mx1, __shfl_xor(mx1, 32, 64));
+    mxrun[0] = fmaxf(mxrun[0], mx0);
+    mxrun[1] = fmaxf(mxrun[1], mx1);
+    if (lane < 32) {        // per (tile, row) maxima: pass 2 skips tiles no row needs
+      float *tm = tab.tile_max + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5) + tile) * tab.NQ + c.n0 + col;
+      if (c.n0 + col < tab.NQ) tm[0] = mx0;
+      if (TWO && c.n0 + 32 + col < tab.NQ) tm[32] = mx1;
+    }
+    const bool over0 = (int)floorf(mx0 * c1) > top[0];
+    const bool over1 = TWO && (int)floorf(mx1 * c1) > top[1];
+    bool event = __any(over0 || over1);          // wave-uniform
+    if (event) {
+      if (lane < 32) {
+        if (over0) atomicMax(&S->newmax[col], ordered_bits(mx0));
+        if (over1) atomicMax(&S->newmax[32 + col], ordered_bits(mx1));
+      }
+      if (lane == 0) *pending = 1;
+    } else {
+      event = __builtin_amdgcn_readfirstlane(pend_seen) != 0;
+    }
+    if (event) sync_event();
+    const bool full = t0 + 32 <= c.t_end;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      if (nb == 0 || TWO) {
+        const float atail = (float)(top[nb] - (kBins - 1));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float d = acc[nb][r];
+          const float af = fmaxf(floorf(d * c1), atail);
+          const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
+          uint32_t u = (uint32_t)(__builtin_amdgcn_exp2f(x) + 0.5f);
+          if (!full) u = t0 + key_of(r, hf) < c.t_end ? u : 0u;
+          atomicAdd(hrow[nb] + (top[nb] - (int)af), u);
+        }
+      }
+    }
+  };
+
+  u32x4 pa[LOADS], pb[LOADS];
+  T.fetch(pa, khead, I.tok_stride, c.t_begin + wave * 32, c.t_end, lane);
+  T.fetch(pb, khead, I.tok_stride, c.t_begin + (wave + kWaves) * 32, c.t_end, lane);
+  for (int tile = wave; tile < n_tiles; tile += 2 * kWaves) {
+    tile_body(pa, tile);
+    if (tile + kWaves < n_tiles) tile_body(pb, tile + kWaves);
   }
-  __syncthreads();
-  if (tid < 64 && c.n0 + tid < tab.NQ)
-    tab.part_max[(size_t)c.slot * tab.NQ + c.n0 + tid] = from_ordered_bits(smax[tid]);
+  if (lane < 32) {
+    atomicMax(&S->rowmax[col], ordered_bits(mxrun[0]));
+    if (TWO) atomicMax(&S->rowmax[32 + col], ordered_bits(mxrun[1]));
+  }
+  // this wave is out of tiles; keep serving the others' events until every wave is
+  if (lane == 0) atomicAdd(&S->done, 1);
+  for (int spins = 0;; ++spins) {
+    if (__builtin_amdgcn_readfirstlane(*pending) != 0) {
+      sync_event();
+      continue;
+    }
+    if (__builtin_amdgcn_readfirstlane(*done) >= kWaves) break;
+    if (spins > (1 << 22)) {          // never reached if the protocol holds; a stuck wave must not hang the GPU
+      S->aborted = 1;
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+  return true;
 }
 
-// ------------------------------------------------------------------ pass B: weight histograms
 template <int DK>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ uint32_t hist[64 * (kBins + 1)];
-  __shared__ int s_top[64];
+  __shared__ HistCtl ctl;
   const WgCoord c = decode_wg(tab, blockIdx.x);
   const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, col = lane & 31;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0u;
   if (tid < 64) {
-    float m = -INFINITY;
-    if (c.n0 + tid < tab.NQ) {
-      const float *pm = tab.part_max + (size_t)(I.part0 + c.kvh * I.n_chunks) * tab.NQ + c.n0 + tid;
-      for (int ch = 0; ch < I.n_chunks; ++ch) m = fmaxf(m, pm[(size_t)ch * tab.NQ]);
-    }
-    s_top[tid] = (int)floorf(m * tab.c1);
+    ctl.top[tid] = kTopUnset;
+    ctl.newmax[tid] = ordered_bits(-3.0e38f);
+    ctl.rowmax[tid] = ordered_bits(-3.0e38f);
   }
-  Tile<DK> T;
-  T.load_q(tab, c.it, c.kvh, c.n0, lane);
-  const bool two = c.n0 + 32 < tab.NQ;
-  const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
+  if (tid == 0) { ctl.pending = 0; ctl.done = 0; ctl.aborted = 0; }
   __syncthreads();
-  const int nblk = two ? 2 : 1;
-  int top[2];
-  uint32_t *hrow[2];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    top[nb] = s_top[32 * nb + col];
-    hrow[nb] = hist + (32 * nb + col) * (kBins + 1);
-  }
-  const float c1 = tab.c1, c2 = tab.c2;
-  // x = d * c2 - (a + 1) * kLog2ePerBin + kFixBits is log2 of the fixed-point term of a key in bin a
-  const float ebias = (float)kFixBits - kLog2ePerBin;
-  float atail[2];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    if (c.n0 + 32 * nb + col >= tab.NQ) top[nb] = 1 << 24;   // rows that do not exist: always the last bin, weight 0
-    atail[nb] = (float)(top[nb] - (kBins - 1));
-  }
-  stream_tiles<DK>(
-      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
-      [&](const floatx16(&acc)[2], int t0, int) __attribute__((always_inline)) {
-        const bool full = t0 + 32 <= c.t_end;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          if (nb < nblk) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float d = acc[nb][r];
-              const float af = fmaxf(floorf(d * c1), atail[nb]);
-              const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
-              uint32_t u = (uint32_t)(__builtin_amdgcn_exp2f(x) + 0.5f);
-              if (!full) u = t0 + key_of(r, hf) < c.t_end ? u : 0u;
-              atomicAdd(hrow[nb] + (top[nb] - (int)af), u);
-            }
-          }
-        }
-      },
-      [](int) {});
+  bool ok;
+  if (c.n0 + 32 < tab.NQ)
+    ok = hist_fused_body<DK, true>(tab, c, I, tiles[wave], hist, &ctl);
+  else
+    ok = hist_fused_body<DK, false>(tab, c, I, tiles[wave], hist, &ctl);
+  if (!ok) return;
   __syncthreads();
-  uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
   const int rows = min(64, tab.NQ - c.n0);
+  if (tid < rows) {
+    tab.part_max[(size_t)c.slot * tab.NQ + c.n0 + tid] = from_ordered_bits(ctl.rowmax[tid]);
+    tab.part_top[(size_t)c.slot * tab.NQ + c.n0 + tid] = ctl.top[tid];
+  }
+  uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
   for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
 }
 
@@ -328,13 +418,42 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   const int j = threadIdx.x, lane = j & 63, wave = j >> 6;
   const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
   float m = -INFINITY;
-  for (int ch = 0; ch < I.n_chunks; ++ch) m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
-  unsigned long long acc = 0ull;
-  for (int ch = 0; ch < I.n_chunks; ++ch) acc += tab.part_hist[((slot0 + ch) * tab.NQ + n) * kBins + j];
-  // weight of bin j relative to exp(max): fixed-point sum * 2^-kFixBits * exp2(edge_j - max), in log2 units
-  const int top = (int)floorf(m * tab.c1);
-  const double edge = (double)(top - j + 1) * (double)kLog2ePerBin;
-  const double mine = ldexp((double)acc, -kFixBits) * exp2(edge - (double)m * (double)tab.c2);
+  int top = kTopUnset;
+  for (int ch = 0; ch < I.n_chunks; ++ch) {
+    m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
+    top = max(top, tab.part_top[(slot0 + ch) * tab.NQ + n]);
+  }
+  // Every chunk binned inside its own window; on the absolute grid its bin jl is global bin
+  // jl + (top - top_chunk).  Weights are fixed-point sums relative to the bin's upper edge, so the
+  // chunks' sums of one absolute bin simply add: mass = sum * 2^-kFixBits * exp2(edge - max) in log2
+  // units.  Chunk bins at or beyond the last global bin (and the chunks' own last bins) are gathered by
+  // thread kBins - 1.
+  const double mref = (double)m * (double)tab.c2;
+  double mine = 0.0;
+  float tailpart = 0.f;    // this thread's share of the last global bin, relative to that bin's edge
+  {
+    unsigned long long acc = 0ull;
+    for (int ch = 0; ch < I.n_chunks; ++ch) {
+      const long long shift = (long long)top - (long long)tab.part_top[(slot0 + ch) * tab.NQ + n];
+      const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
+      const long long jl = (long long)j - shift;
+      if (j < kBins - 1 && jl >= 0) acc += hc[jl];
+      // chunk bin j of this chunk, if it lies at or beyond the last global bin
+      const long long over = (long long)j + shift - (kBins - 1);
+      if (over >= 0) {
+        const uint32_t u = hc[j];
+        if (u) tailpart += (float)u * __builtin_amdgcn_exp2f(-(float)over * kLog2ePerBin);
+      }
+    }
+    if (acc) mine = ldexp((double)acc, -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref);
+  }
+  __shared__ float tsum[4];
+  for (int off = 32; off > 0; off >>= 1) tailpart += __shfl_xor(tailpart, off, 64);
+  if (lane == 0) tsum[wave] = tailpart;
+  __syncthreads();
+  if (j == kBins - 1)
+    mine = ldexp((double)(tsum[0] + tsum[1] + tsum[2] + tsum[3]), -kFixBits) *
+           exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
   // inclusive scan over bins (bin 0 = highest logits)
   __shared__ double wsum[4];
   double x = mine;
@@ -353,7 +472,7 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   RowInfo *info = tab.info + grow;
   if (before < target && cum >= target) {
     info->mdot = m;
-    info->astar = (int)floorf(m * tab.c1) - j;
+    info->astar = top - j;
     info->flag = (j == kBins - 1) ? 1 : 0;
     info->above = before;
     info->target = target;
@@ -367,19 +486,168 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   }
 }
 
-// ------------------------------------------------------------------ pass C: masks + boundary candidates
+// ------------------------------------------------------------------ pass 2: masks + boundary candidates
+// Pass 1 left the maximum of every (tile, row).  A tile in which no row reaches its cut bin selects
+// nothing, so its keys are not even fetched: the second K read shrinks to the tiles that matter
+// (attention mass is concentrated, most tiles hold no selected key for any of the 64 rows).
+struct EmitShared {
+  uint32_t mwords[64][kWaves * kRoundTiles + 1];
+  uint2 cbuf[64][kLocalCand];
+  int ccnt[64];
+  int cbase[64];
+  int astar[64];
+  int row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
+};
+
+template <int DK, bool TWO>
+__device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
+                                          unsigned char *ldstile, EmitShared *E) {
+  constexpr int LOADS = Tile<DK>::LOADS;
+  constexpr int kRoundWords = kWaves * kRoundTiles;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
+            col = lane & 31;
+  const int row_base = c.it * tab.rows_per_item;
+  Tile<DK> T;
+  T.load_q(tab, c.it, c.kvh, c.n0, lane);
+  const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
+  const float c1 = tab.c1;
+  const int astar[2] = {E->astar[col], E->astar[32 + col]};
+  const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
+  const int n_rounds = (n_tiles + kRoundWords - 1) / kRoundWords;
+  const int nk = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave (<= 32)
+
+  // which of my tiles can hold a key at or above some row's cut bin (half a bin of margin)?
+  uint32_t need = 0u;
+  {
+    const int a_l = E->astar[lane];
+    const float dcut_l = a_l == 0x7FFFFFFF ? INFINITY : ((float)a_l - 0.5f) / c1;
+    const float *tm = tab.tile_max + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5)) * tab.NQ + c.n0 + lane;
+    const bool row_ok = c.n0 + lane < tab.NQ;
+    for (int k = 0; k < nk; ++k) {
+      const float v = row_ok ? tm[(size_t)(wave + kWaves * k) * tab.NQ] : -INFINITY;
+      if (__any(v >= dcut_l)) need |= 1u << k;
+    }
+  }
+
+  auto round_end = [&](int round) __attribute__((always_inline)) {
+    const int round0 = c.t_begin + round * kRoundKeys;
+    __syncthreads();
+    // mask words of this round: every row writes one contiguous run of up to 128 bytes
+    const int w_first = round0 >> 5;
+    const int n_words = min(kRoundWords, ((c.t_end - round0) + 31) >> 5);
+    for (int i = tid; i < 64 * kRoundWords; i += kThreads) {
+      const int nl = i / kRoundWords, w = i % kRoundWords;
+      const int r = E->row[nl];
+      if (r >= 0 && w < n_words) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = E->mwords[nl][w];
+    }
+    // boundary candidates of this round -> the rows' global lists
+    if (tid < 64) {
+      const int cnt = E->ccnt[tid];
+      const int r = E->row[tid];
+      E->cbase[tid] = -1;
+      if (r >= 0 && cnt > 0) {
+        if (cnt > kLocalCand) {
+          tab.info[row_base + r].flag = 1;
+        } else {
+          const int b = atomicAdd(&tab.cand_cnt[row_base + r], cnt);
+          if (b + cnt <= kCandCap) E->cbase[tid] = b;   // else resolve sees the count and flags the row
+        }
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < 64 * kLocalCand; i += kThreads) {
+      const int nl = i / kLocalCand, sl = i % kLocalCand;
+      const int b = E->cbase[nl];
+      if (b >= 0 && sl < E->ccnt[nl]) tab.cands[(size_t)(row_base + E->row[nl]) * kCandCap + b + sl] = E->cbuf[nl][sl];
+    }
+    for (int i = tid; i < 64 * kRoundWords; i += kThreads) E->mwords[i / kRoundWords][i % kRoundWords] = 0u;
+    __syncthreads();
+    if (tid < 64) E->ccnt[tid] = 0;
+    __syncthreads();
+  };
+
+  int cur_round = 0;
+  uint32_t todo = need;        // tiles not yet fetched
+  auto next_k = [&]() __attribute__((always_inline)) -> int {
+    if (todo == 0u) return -1;
+    const int k = __ffs(todo) - 1;
+    todo &= todo - 1u;
+    return k;
+  };
+  auto process = [&](u32x4(&pre)[LOADS], int k, int k_refill) __attribute__((always_inline)) {
+    while (cur_round < k / kRoundTiles) round_end(cur_round++);
+    const int tile = wave + kWaves * k;
+    const int t0 = c.t_begin + tile * 32;
+    T.stage(pre, ldstile, lane);
+    if (k_refill >= 0) T.fetch(pre, khead, I.tok_stride, c.t_begin + (wave + kWaves * k_refill) * 32, c.t_end, lane);
+    __builtin_amdgcn_wave_barrier();
+    floatx16 acc[2];
+    T.template compute<TWO>(acc, ldstile, lane);
+    __builtin_amdgcn_wave_barrier();
+    const bool full = t0 + 32 <= c.t_end;
+    // floor(d * c1) >= astar  <=>  d * c1 >= astar (astar is an integer): two compares, no floor
+    uint32_t ge[2] = {0u, 0u}, gt[2] = {0u, 0u};
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      if (nb == 0 || TWO) {
+        const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key_of(r, hf);
+          const float x = acc[nb][r] * c1;
+          const bool valid = full || t0 + key < c.t_end;
+          ge[nb] |= (valid && x >= lo) ? (1u << key) : 0u;
+          gt[nb] |= (valid && x >= hi) ? (1u << key) : 0u;
+        }
+      }
+    }
+    if (__any(((ge[0] & ~gt[0]) | (ge[1] & ~gt[1])) != 0u)) {   // keys inside a cut bin: rare
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const uint32_t cm = ge[nb] & ~gt[nb];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (cm & (1u << key_of(r, hf))) {
+            const int nl = 32 * nb + col;
+            const int slot = atomicAdd(&E->ccnt[nl], 1);
+            if (slot < kLocalCand)
+              E->cbuf[nl][slot] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
+          }
+        }
+      }
+    }
+    const int widx = (k % kRoundTiles) * kWaves + wave;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const uint32_t w = gt[nb] | __shfl_xor(gt[nb], 32, 64);
+      if (lane < 32 && w != 0u) E->mwords[32 * nb + lane][widx] = w;
+    }
+  };
+
+  u32x4 pa[LOADS], pb[LOADS];
+  int ka = next_k(), kb = next_k();
+  if (ka >= 0) T.fetch(pa, khead, I.tok_stride, c.t_begin + (wave + kWaves * ka) * 32, c.t_end, lane);
+  if (kb >= 0) T.fetch(pb, khead, I.tok_stride, c.t_begin + (wave + kWaves * kb) * 32, c.t_end, lane);
+  while (ka >= 0) {
+    const int ka2 = next_k();
+    process(pa, ka, ka2);
+    if (kb >= 0) {
+      const int kb2 = next_k();
+      process(pb, kb, kb2);
+      kb = kb2;
+    }
+    ka = ka2;
+  }
+  while (cur_round < n_rounds) round_end(cur_round++);
+}
+
 template <int DK>
 __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
-  __shared__ uint32_t mwords[64][kWaves * kRoundTiles + 1];
-  __shared__ uint2 cbuf[64][kLocalCand];
-  __shared__ int ccnt[64];
-  __shared__ int cbase[64];
-  __shared__ int s_astar[64];
-  __shared__ int s_row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
+  __shared__ EmitShared E;
   const WgCoord c = decode_wg(tab, blockIdx.x);
   const FastItem I = tab.it[c.it];
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, col = lane & 31;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int row_base = c.it * tab.rows_per_item;   // batch-local row index of (s = 0, h = 0)
   if (tid < 64) {
     const int n = c.n0 + tid;
@@ -389,109 +657,16 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
       r = s * tab.Hq + c.kvh * tab.G + g;
       a = tab.info[row_base + r].astar;
     }
-    s_astar[tid] = a;
-    s_row[tid] = r;
-    ccnt[tid] = 0;
+    E.astar[tid] = a;
+    E.row[tid] = r;
+    E.ccnt[tid] = 0;
   }
-  Tile<DK> T;
-  T.load_q(tab, c.it, c.kvh, c.n0, lane);
-  const bool two = c.n0 + 32 < tab.NQ;
-  const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
+  for (int i = tid; i < 64 * (kWaves * kRoundTiles + 1); i += kThreads) (&E.mwords[0][0])[i] = 0u;
   __syncthreads();
-  int astar[2];
-  astar[0] = s_astar[col];
-  astar[1] = s_astar[32 + col];
-  const float c1 = tab.c1;
-  const int nblk = two ? 2 : 1;
-  constexpr int kRoundWords = kWaves * kRoundTiles;
-  // raw dot below which a key surely lies under the row's cut bin (half a bin of margin; rows that do
-  // not exist carry astar = INT_MAX and never match)
-  float dcut[2];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) dcut[nb] = astar[nb] == 0x7FFFFFFF ? INFINITY : ((float)astar[nb] - 0.5f) / c1;
-
-  stream_tiles<DK>(
-      T, tiles[wave], khead, I.tok_stride, c.t_begin, c.t_end, wave, lane, two,
-      [&](const floatx16(&acc)[2], int t0, int k) __attribute__((always_inline)) {
-        uint32_t bits[2] = {0u, 0u};
-        const bool full = t0 + 32 <= c.t_end;
-        // most tiles hold no key at or above any row's cut bin: one max per row settles that
-        float mx0 = acc[0][0], mx1 = acc[1][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) { mx0 = fmaxf(mx0, acc[0][r]); mx1 = fmaxf(mx1, acc[1][r]); }
-        const bool near = mx0 >= dcut[0] || mx1 >= dcut[1];
-        if (__any(near)) {
-          uint32_t cmask[2] = {0u, 0u};
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
-            if (nb < nblk) {
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int key = key_of(r, hf);
-                const bool valid = full || t0 + key < c.t_end;
-                const int a = (int)floorf(acc[nb][r] * c1);
-                bits[nb] |= (valid && a > astar[nb]) ? (1u << key) : 0u;
-                cmask[nb] |= (valid && a == astar[nb]) ? (1u << r) : 0u;
-              }
-            }
-          }
-          if (__any((cmask[0] | cmask[1]) != 0u)) {   // keys inside the cut bin: rare
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                if (cmask[nb] & (1u << r)) {
-                  const int nl = 32 * nb + col;
-                  const int slot = atomicAdd(&ccnt[nl], 1);
-                  if (slot < kLocalCand)
-                    cbuf[nl][slot] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
-                }
-              }
-            }
-          }
-        }
-        const int widx = (k % kRoundTiles) * kWaves + wave;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          const uint32_t w = bits[nb] | __shfl_xor(bits[nb], 32, 64);
-          if (lane < 32) mwords[32 * nb + lane][widx] = w;
-        }
-      },
-      [&](int round) __attribute__((always_inline)) {
-        const int round0 = c.t_begin + round * kRoundKeys;
-        __syncthreads();
-        // mask words of this round: every row writes one contiguous run of up to 128 bytes
-        const int w_first = round0 >> 5;
-        const int n_words = min(kRoundWords, ((c.t_end - round0) + 31) >> 5);
-        for (int i = tid; i < 64 * kRoundWords; i += kThreads) {
-          const int nl = i / kRoundWords, w = i % kRoundWords;
-          const int r = s_row[nl];
-          if (r >= 0 && w < n_words) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = mwords[nl][w];
-        }
-        // boundary candidates of this round -> the rows' global lists
-        if (tid < 64) {
-          const int cnt = ccnt[tid];
-          const int r = s_row[tid];
-          cbase[tid] = -1;
-          if (r >= 0 && cnt > 0) {
-            if (cnt > kLocalCand) {
-              tab.info[row_base + r].flag = 1;
-            } else {
-              const int b = atomicAdd(&tab.cand_cnt[row_base + r], cnt);
-              if (b + cnt <= kCandCap) cbase[tid] = b;   // else resolve sees the count and flags the row
-            }
-          }
-        }
-        __syncthreads();
-        for (int i = tid; i < 64 * kLocalCand; i += kThreads) {
-          const int nl = i / kLocalCand, sl = i % kLocalCand;
-          const int b = cbase[nl];
-          if (b >= 0 && sl < ccnt[nl]) tab.cands[(size_t)(row_base + s_row[nl]) * kCandCap + b + sl] = cbuf[nl][sl];
-        }
-        __syncthreads();
-        if (tid < 64) ccnt[tid] = 0;
-        __syncthreads();
-      });
+  if (c.n0 + 32 < tab.NQ)
+    emit_body<DK, true>(tab, c, I, tiles[wave], &E);
+  else
+    emit_body<DK, false>(tab, c, I, tiles[wave], &E);
 }
 
 // ------------------------------------------------------------------ per row: exact cut among the candidates
@@ -581,22 +756,28 @@ bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p) {
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S) {
   FastPlan pl;
   const int NQ = S * (sh->n_q_heads / sh->n_kv_heads);
-  size_t max_slots = 0, max_rows = 0;
+  size_t max_slots = 0, max_rows = 0, max_tiles = 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
     const int ck = pick_chunk_keys(sh, items + b0, nb);
-    size_t slots = 0;
-    for (int i = 0; i < nb; ++i) slots += (size_t)sh->n_kv_heads * ceil_div(items[b0 + i].L, ck);
+    size_t slots = 0, tiles = 0;
+    for (int i = 0; i < nb; ++i) {
+      slots += (size_t)sh->n_kv_heads * ceil_div(items[b0 + i].L, ck);
+      tiles += (size_t)sh->n_kv_heads * ((items[b0 + i].L + 31) / 32);
+    }
     if (slots > max_slots) max_slots = slots;
+    if (tiles > max_tiles) max_tiles = tiles;
     const size_t rows = (size_t)nb * S * sh->n_q_heads;
     if (rows > max_rows) max_rows = rows;
   }
   pl.off_max = 256;   // the first 256 bytes hold the fallback-row counter
-  pl.off_hist = pl.off_max + align_up(max_slots * NQ * sizeof(float), 256);
+  pl.off_top = pl.off_max + align_up(max_slots * NQ * sizeof(float), 256);
+  pl.off_hist = pl.off_top + align_up(max_slots * NQ * sizeof(int), 256);
   pl.off_info = pl.off_hist + align_up(max_slots * NQ * kBins * sizeof(float), 256);
   pl.off_cnt = pl.off_info + align_up(max_rows * sizeof(RowInfo), 256);
   pl.off_cands = pl.off_cnt + align_up(max_rows * sizeof(int), 256);
-  pl.ws_bytes = pl.off_cands + align_up(max_rows * kCandCap * sizeof(uint2), 256);
+  pl.off_tmax = pl.off_cands + align_up(max_rows * kCandCap * sizeof(uint2), 256);
+  pl.ws_bytes = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
   return pl;
 }
 
@@ -621,34 +802,34 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.q = q; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.part_max = reinterpret_cast<float *>(wsb + pl.off_max);
+    tab.part_top = reinterpret_cast<int *>(wsb + pl.off_top);
+    tab.tile_max = reinterpret_cast<float *>(wsb + pl.off_tmax);
     tab.part_hist = reinterpret_cast<uint32_t *>(wsb + pl.off_hist);
     tab.info = reinterpret_cast<RowInfo *>(wsb + pl.off_info);
     tab.cand_cnt = reinterpret_cast<int *>(wsb + pl.off_cnt);
     tab.cands = reinterpret_cast<uint2 *>(wsb + pl.off_cands);
     int wg = 0, part = 0;
+    long long tmax0 = 0;
     for (int i = 0; i < nb; ++i) {
       const gvote_item &g = items[b0 + i];
       FastItem &f = tab.it[i];
       f.k = g.k; f.tok_stride = g.kv_tok_stride; f.head_stride = g.kv_head_stride;
       f.mask_off = mask_off; f.L = g.L; f.W = (g.L + 31) / 32;
       f.n_chunks = ceil_div(g.L, tab.chunk_keys);
-      f.wg0 = wg; f.part0 = part; f.pad = 0;
+      f.wg0 = wg; f.part0 = part; f.pad = 0; f.tmax0 = tmax0;
+      tmax0 += (long long)sh->n_kv_heads * f.W * tab.NQ;
       wg += sh->n_kv_heads * f.n_chunks * tab.NQB;
       part += sh->n_kv_heads * f.n_chunks;
       mask_off += (long long)tab.rows_per_item * f.W;
     }
     const int rows = nb * tab.rows_per_item;
     if (sh->head_dim == 128) {
-      hipLaunchKernelGGL(score_max_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
-      GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_hist_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(rows), dim3(kBins), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_emit_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
     } else {
-      hipLaunchKernelGGL(score_max_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
-      GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_hist_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(rows), dim3(kBins), 0, st, tab);
