@@ -65,6 +65,10 @@ def main():
     ap.add_argument("--items", type=int, default=0, help="use only the first N items (debug)")
     ap.add_argument("--cpu-sample", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc runs, already scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -117,7 +121,8 @@ def main():
     ab = algorithmic_bytes(wl, wl.lengths, rho)
     dom = max(stage_ms, key=stage_ms.get)
     dom_kernel = {"fit": "moments_partial_kernel", "sample": "project_mfma_kernel",
-                  "select": "select_row_kernel", "compact": "gather_kernel"}[dom]
+                  "select": "score_hist_kernel", "compact": "gather_kernel"}[dom]
+    traffic = None if args.traffic_kib is None else (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
     ach = ab[dom] / (stage_ms[dom] * 1e-3) / 1e9
     out = {
         "metric": "KV tokens selected+compacted/sec (all layers, 32k ctx); achieved HBM GB/s vs peak",
@@ -129,7 +134,8 @@ def main():
         "config": {"workload": wl.name, "items": wl.n_items, "L": max(wl.lengths), "S": wl.S, "p": wl.p,
                    "d_model": wl.d, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads, "head_dim": wl.d_k},
         "roofline": {"bound": "hbm", "kernel": dom_kernel, "stage": dom, "achieved": ach, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes": ab[dom], "ms": stage_ms[dom]},
         "end_to_end": {"algorithmic_GB": ab["total"] / 1e9,
                        "achieved_GBs": ab["total"] / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
@@ -141,6 +147,14 @@ def main():
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,
     }
+    if args.copy_probe:
+        a = torch.empty(1 << 30, device=dev, dtype=torch.uint8)
+        bb = torch.empty_like(a)
+        a.fill_(1)
+        torch.cuda.synchronize()
+        bb.copy_(a)
+        torch.cuda.synchronize()
+        del a, bb
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, items, min(args.cpu_sample, wl.n_items))
     print(json.dumps(out))
