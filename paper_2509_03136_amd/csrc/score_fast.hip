@@ -4,16 +4,16 @@
 // Nothing of size S*H_q*L is stored: logits are recomputed from K in each pass, bit-identically
 // (same MFMA sequence), and only per-row statistics travel between the passes.
 //
-//   score_max    pass A: per (item, KV head, key chunk) the maximum raw dot product of every
-//                query row of the group.
-//   score_hist   pass B: weight exp(l - m) of every key accumulated into 256 bins of width 1/16
-//                in logit units below the row maximum, per row, in LDS; the last bin collects
-//                everything further down.
+//   score_hist   pass 1 over K: per (item, KV head, key chunk) the row maxima and, in LDS, a 256-bin
+//                fixed-point histogram per query row of the weight exp(l) on an absolute grid of
+//                1/16 logit; the window of bins slides up with the running maximum.  Also leaves the
+//                per (32-key tile, row) maxima.
 //   find_bin     per row: merge the chunks, Z, target p*Z, walk the bins from the top: the bin
 //                a* where the cumulative weight crosses the target, and the weight above it.
-//   score_emit   pass C: keys in bins above a* are selected outright (bit masks, transposed in
-//                LDS so every row writes whole 128-byte lines); keys inside bin a* are appended
-//                (raw dot, position) to the row's candidate list.
+//   score_emit   pass 2 over K, only over tiles whose maxima reach some row's cut bin: keys in bins
+//                above a* are selected outright (bit masks, transposed in LDS so every row writes
+//                whole 128-byte runs); keys inside bin a* are appended (raw dot, position) to the
+//                row's candidate list.
 //   resolve      per row: exact selection among the candidates - radix search over the 64-bit
 //                key (ordered dot, ~position), so ties go to the lower position - and OR of the
 //                chosen bits into the mask.
@@ -59,6 +59,24 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u) {
 // < 1.2e-7 of the maximum each; below 2^-19 of the edge they round to nothing).
 constexpr int kFixBits = 18;
 constexpr float kLog2ePerBin = 1.44269504088896340736f / (float)kBinsPerUnit;   // log2 weight per bin
+
+// integer add to a 32-bit word of LDS given its byte address inside the workgroup's LDS
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+__device__ __forceinline__ void lds_add_u32(uint32_t byte_addr, uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __hip_atomic_fetch_add((lds_u32 *)(size_t)byte_addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#else
+  (void)byte_addr; (void)v;
+#endif
+}
+// byte offset of an LDS object inside the workgroup's LDS
+__device__ __forceinline__ int lds_offset(const void *p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return (int)(size_t)(const __attribute__((address_space(3))) char *)p;
+#else
+  (void)p; return 0;
+#endif
+}
 
 // position of accumulator register r of lane (hf = lane / 32) inside the 32-key tile
 __device__ __forceinline__ int key_of(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
@@ -135,22 +153,27 @@ struct Tile {
     }
   }
 
-  // all eight A operands are read before the first MFMA so the LDS latency is paid once per tile
+  // the A operands are read four k-steps at a time ahead of their MFMAs: the LDS latency is paid twice
+  // per tile and only 16 registers hold operands
   template <bool TWO>
   __device__ __forceinline__ void compute(floatx16 (&acc)[2], const unsigned char *lds, int lane) const {
     const int key = lane & 31, hf = lane >> 5;
-    bf16x8 a[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int phys = (2 * ks + hf) ^ (key & (PPR - 1));
-      a[ks] = *reinterpret_cast<const bf16x8 *>(lds + (key * PPR + phys) * 16);
-    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
+    constexpr int GRP = KS < 4 ? KS : 4;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[0][ks], acc[0], 0, 0, 0);
-      if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bq[1][ks], acc[1], 0, 0, 0);
+    for (int k0 = 0; k0 < KS; k0 += GRP) {
+      bf16x8 a[GRP];
+#pragma unroll
+      for (int i = 0; i < GRP; ++i) {
+        const int phys = (2 * (k0 + i) + hf) ^ (key & (PPR - 1));
+        a[i] = *reinterpret_cast<const bf16x8 *>(lds + (key * PPR + phys) * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < GRP; ++i) {
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bq[0][k0 + i], acc[0], 0, 0, 0);
+        if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bq[1][k0 + i], acc[1], 0, 0, 0);
+      }
     }
   }
 };
@@ -299,7 +322,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
     // joined at the next tile (its barrier waits for this wave, so the histogram stays put meanwhile)
     const int pend_seen = *pending;
     T.stage(pre, ldstile, lane);
-    if (tile + 2 * kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + 2 * kWaves * 32, c.t_end, lane);
+    if (tile + kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + kWaves * 32, c.t_end, lane);
     __builtin_amdgcn_wave_barrier();
     T.template compute<TWO>(acc, ldstile, lane);
     __builtin_amdgcn_wave_barrier();
@@ -329,31 +352,48 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
       event = __builtin_amdgcn_readfirstlane(pend_seen) != 0;
     }
     if (event) sync_event();
-    const bool full = t0 + 32 <= c.t_end;
+    // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 18),
+    // truncated (a uniform -2e-6 relative bias that cancels in every ratio of sums); LDS byte address
+    // hrow + 4 (top - a), formed in fp32 (exact: all quantities are small integers).
+    if (t0 + 32 <= c.t_end) {
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      if (nb == 0 || TWO) {
-        const float atail = (float)(top[nb] - (kBins - 1));
+      for (int nb = 0; nb < 2; ++nb) {
+        if (nb == 0 || TWO) {
+          const float atail = (float)(top[nb] - (kBins - 1));
+          const float abase = (float)(lds_offset(hrow[nb]) + 4 * top[nb]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float d = acc[nb][r];
-          const float af = fmaxf(floorf(d * c1), atail);
-          const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
-          uint32_t u = (uint32_t)(__builtin_amdgcn_exp2f(x) + 0.5f);
-          if (!full) u = t0 + key_of(r, hf) < c.t_end ? u : 0u;
-          atomicAdd(hrow[nb] + (top[nb] - (int)af), u);
+          for (int r = 0; r < 16; ++r) {
+            const float d = acc[nb][r];
+            const float af = fmaxf(floorf(d * c1), atail);
+            const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
+            const uint32_t u = (uint32_t)__builtin_amdgcn_exp2f(x);
+            lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
+            if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's look-ahead (registers)
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        if (nb == 0 || TWO) {
+          const float atail = (float)(top[nb] - (kBins - 1));
+          const float abase = (float)(lds_offset(hrow[nb]) + 4 * top[nb]);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float d = acc[nb][r];
+            const float af = fmaxf(floorf(d * c1), atail);
+            const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
+            const uint32_t u = t0 + key_of(r, hf) < c.t_end ? (uint32_t)__builtin_amdgcn_exp2f(x) : 0u;
+            lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
+          }
         }
       }
     }
   };
 
-  u32x4 pa[LOADS], pb[LOADS];
+  u32x4 pa[LOADS];
   T.fetch(pa, khead, I.tok_stride, c.t_begin + wave * 32, c.t_end, lane);
-  T.fetch(pb, khead, I.tok_stride, c.t_begin + (wave + kWaves) * 32, c.t_end, lane);
-  for (int tile = wave; tile < n_tiles; tile += 2 * kWaves) {
-    tile_body(pa, tile);
-    if (tile + kWaves < n_tiles) tile_body(pb, tile + kWaves);
-  }
+  for (int tile = wave; tile < n_tiles; tile += kWaves) tile_body(pa, tile);
   if (lane < 32) {
     atomicMax(&S->rowmax[col], ordered_bits(mxrun[0]));
     if (TWO) atomicMax(&S->rowmax[32 + col], ordered_bits(mxrun[1]));
