@@ -189,6 +189,7 @@ struct ScorePlan { size_t ws_bytes; };
 constexpr int kBins = 256;            // histogram bins per row below the row maximum
 constexpr int kBinsPerUnit = 16;      // bins per unit of logit: bin width 1/16, window 16 units
 constexpr int kCandCap = 1024;        // boundary-bin candidates a row may collect before it is redone exactly
+constexpr int kSubCap = 8;            // entries of one candidate sub-list (row, key chunk, wave, lane half)
 struct RowInfo {
   float mdot;       // row maximum of the raw dot product
   int astar;        // absolute bin index floor(dot * c1) in which the cut falls
@@ -211,6 +212,7 @@ struct FastItem {
 struct FastTable {
   int n_items, S, Hq, Hkv, G, NQ, NQB, chunk_keys;
   int item0, rows_per_item;
+  int sub_per_row, pad0;    // candidate sub-lists per row = 16 * (most key chunks of an item in the batch)
   float scale, c1, c2, p;   // c1 = bins per raw-dot unit, c2 = log2(e) / sqrt(d_k)
   const void *q;
   uint32_t *rowmask;
@@ -221,8 +223,8 @@ struct FastTable {
   float *tile_max;          // per (item, KV head, 32-key tile, row): maximum raw dot, written by pass 1
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
-  int *cand_cnt;            // [rows]
-  uint2 *cands;             // [rows][kCandCap]: (raw dot bits, position)
+  int *cand_cnt;            // [rows][sub_per_row]: entries in each sub-list
+  uint2 *cands;             // [rows][sub_per_row][kSubCap]: (raw dot bits, position)
   FastItem it[kMaxItems];
 };
 struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, ws_bytes; };

@@ -519,7 +519,6 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   }
   if (j == 0) {
     if (grow == 0 && tab.item0 == 0) *tab.n_fallback = 0;
-    tab.cand_cnt[grow] = 0;
     const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
     if (tab.row_max) tab.row_max[gr] = m * tab.scale;
     if (tab.row_sum) tab.row_sum[gr] = (float)Z;
@@ -530,11 +529,9 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
 // Pass 1 left the maximum of every (tile, row).  A tile in which no row reaches its cut bin selects
 // nothing, so its keys are not even fetched: the second K read shrinks to the tiles that matter
 // (attention mass is concentrated, most tiles hold no selected key for any of the 64 rows).
+constexpr int kMaxChunkWords = 8 * kRoundKeys / 32;     // mask words per row of the largest chunk (256)
 struct EmitShared {
-  uint32_t mwords[64][kWaves * kRoundTiles + 1];
-  uint2 cbuf[64][kLocalCand];
-  int ccnt[64];
-  int cbase[64];
+  uint32_t mwords[64][kMaxChunkWords + 1];
   int astar[64];
   int row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
 };
@@ -543,7 +540,6 @@ template <int DK, bool TWO>
 __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
                                           unsigned char *ldstile, EmitShared *E) {
   constexpr int LOADS = Tile<DK>::LOADS;
-  constexpr int kRoundWords = kWaves * kRoundTiles;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
             col = lane & 31;
   const int row_base = c.it * tab.rows_per_item;
@@ -552,8 +548,8 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
   const float c1 = tab.c1;
   const int astar[2] = {E->astar[col], E->astar[32 + col]};
+  const int grow[2] = {row_base + E->row[col], row_base + E->row[32 + col]};   // only used for rows that exist
   const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
-  const int n_rounds = (n_tiles + kRoundWords - 1) / kRoundWords;
   const int nk = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave (<= 32)
 
   // which of my tiles can hold a key at or above some row's cut bin (half a bin of margin)?
@@ -563,50 +559,25 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     const float dcut_l = a_l == 0x7FFFFFFF ? INFINITY : ((float)a_l - 0.5f) / c1;
     const float *tm = tab.tile_max + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5)) * tab.NQ + c.n0 + lane;
     const bool row_ok = c.n0 + lane < tab.NQ;
-    for (int k = 0; k < nk; ++k) {
-      const float v = row_ok ? tm[(size_t)(wave + kWaves * k) * tab.NQ] : -INFINITY;
-      if (__any(v >= dcut_l)) need |= 1u << k;
-    }
+    // all loads first (independent, in flight together), then the votes
+    constexpr int kMaxK = 32;          // chunk_keys <= 8192 -> at most 32 tiles per wave
+    float v[kMaxK];
+#pragma unroll
+    for (int k = 0; k < kMaxK; ++k)
+      v[k] = (row_ok && k < nk) ? tm[(size_t)(wave + kWaves * k) * tab.NQ] : -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kMaxK; ++k)
+      if (__any(v[k] >= dcut_l)) need |= 1u << k;
   }
 
-  auto round_end = [&](int round) __attribute__((always_inline)) {
-    const int round0 = c.t_begin + round * kRoundKeys;
-    __syncthreads();
-    // mask words of this round: every row writes one contiguous run of up to 128 bytes
-    const int w_first = round0 >> 5;
-    const int n_words = min(kRoundWords, ((c.t_end - round0) + 31) >> 5);
-    for (int i = tid; i < 64 * kRoundWords; i += kThreads) {
-      const int nl = i / kRoundWords, w = i % kRoundWords;
-      const int r = E->row[nl];
-      if (r >= 0 && w < n_words) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = E->mwords[nl][w];
-    }
-    // boundary candidates of this round -> the rows' global lists
-    if (tid < 64) {
-      const int cnt = E->ccnt[tid];
-      const int r = E->row[tid];
-      E->cbase[tid] = -1;
-      if (r >= 0 && cnt > 0) {
-        if (cnt > kLocalCand) {
-          tab.info[row_base + r].flag = 1;
-        } else {
-          const int b = atomicAdd(&tab.cand_cnt[row_base + r], cnt);
-          if (b + cnt <= kCandCap) E->cbase[tid] = b;   // else resolve sees the count and flags the row
-        }
-      }
-    }
-    __syncthreads();
-    for (int i = tid; i < 64 * kLocalCand; i += kThreads) {
-      const int nl = i / kLocalCand, sl = i % kLocalCand;
-      const int b = E->cbase[nl];
-      if (b >= 0 && sl < E->ccnt[nl]) tab.cands[(size_t)(row_base + E->row[nl]) * kCandCap + b + sl] = E->cbuf[nl][sl];
-    }
-    for (int i = tid; i < 64 * kRoundWords; i += kThreads) E->mwords[i / kRoundWords][i % kRoundWords] = 0u;
-    __syncthreads();
-    if (tid < 64) E->ccnt[tid] = 0;
-    __syncthreads();
-  };
+  // Candidate sub-lists: one per (row, key chunk, wave, lane half), written by exactly one lane, so the
+  // count lives in a register and nothing waits on an atomic's return.
+  const int sub = (c.chunk * kWaves + wave) * 2 + hf;
+  int ccount[2] = {0, 0};
+  uint2 *cdst[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) cdst[nb] = tab.cands + ((size_t)grow[nb] * tab.sub_per_row + sub) * kSubCap;
 
-  int cur_round = 0;
   uint32_t todo = need;        // tiles not yet fetched
   auto next_k = [&]() __attribute__((always_inline)) -> int {
     if (todo == 0u) return -1;
@@ -614,8 +585,9 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     todo &= todo - 1u;
     return k;
   };
+  // No workgroup barrier inside the loop: waves with few tiles to look at finish early, the time of the
+  // pass follows the number of tiles that matter.
   auto process = [&](u32x4(&pre)[LOADS], int k, int k_refill) __attribute__((always_inline)) {
-    while (cur_round < k / kRoundTiles) round_end(cur_round++);
     const int tile = wave + kWaves * k;
     const int t0 = c.t_begin + tile * 32;
     T.stage(pre, ldstile, lane);
@@ -624,43 +596,57 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     floatx16 acc[2];
     T.template compute<TWO>(acc, ldstile, lane);
     __builtin_amdgcn_wave_barrier();
-    const bool full = t0 + 32 <= c.t_end;
     // floor(d * c1) >= astar  <=>  d * c1 >= astar (astar is an integer): two compares, no floor
     uint32_t ge[2] = {0u, 0u}, gt[2] = {0u, 0u};
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      if (nb == 0 || TWO) {
-        const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key_of(r, hf);
-          const float x = acc[nb][r] * c1;
-          const bool valid = full || t0 + key < c.t_end;
-          ge[nb] |= (valid && x >= lo) ? (1u << key) : 0u;
-          gt[nb] |= (valid && x >= hi) ? (1u << key) : 0u;
-        }
-      }
-    }
-    if (__any(((ge[0] & ~gt[0]) | (ge[1] & ~gt[1])) != 0u)) {   // keys inside a cut bin: rare
+    if (t0 + 32 <= c.t_end) {
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        const uint32_t cm = ge[nb] & ~gt[nb];
+        if (nb == 0 || TWO) {
+          const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          if (cm & (1u << key_of(r, hf))) {
-            const int nl = 32 * nb + col;
-            const int slot = atomicAdd(&E->ccnt[nl], 1);
-            if (slot < kLocalCand)
-              E->cbuf[nl][slot] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
+          for (int r = 0; r < 16; ++r) {
+            const float x = acc[nb][r] * c1;
+            ge[nb] |= x >= lo ? (1u << key_of(r, hf)) : 0u;
+            gt[nb] |= x >= hi ? (1u << key_of(r, hf)) : 0u;
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        if (nb == 0 || TWO) {
+          const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = key_of(r, hf);
+            const float x = acc[nb][r] * c1;
+            const bool valid = t0 + key < c.t_end;
+            ge[nb] |= (valid && x >= lo) ? (1u << key) : 0u;
+            gt[nb] |= (valid && x >= hi) ? (1u << key) : 0u;
           }
         }
       }
     }
-    const int widx = (k % kRoundTiles) * kWaves + wave;
+    const uint32_t cm[2] = {ge[0] & ~gt[0], ge[1] & ~gt[1]};
+    if (__any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        if (cm[nb]) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            if (cm[nb] & (1u << key_of(r, hf))) {
+              if (ccount[nb] < kSubCap)
+                cdst[nb][ccount[nb]] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
+              ++ccount[nb];
+            }
+          }
+        }
+      }
+    }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       const uint32_t w = gt[nb] | __shfl_xor(gt[nb], 32, 64);
-      if (lane < 32 && w != 0u) E->mwords[32 * nb + lane][widx] = w;
+      if (lane < 32 && w != 0u) E->mwords[32 * nb + lane][tile] = w;
     }
   };
 
@@ -678,7 +664,21 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     }
     ka = ka2;
   }
-  while (cur_round < n_rounds) round_end(cur_round++);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    if ((nb == 0 || TWO) && c.n0 + 32 * nb + col < tab.NQ) {
+      tab.cand_cnt[(size_t)grow[nb] * tab.sub_per_row + sub] = min(ccount[nb], kSubCap);
+      if (ccount[nb] > kSubCap) tab.info[grow[nb]].flag = 1;   // the exact selector redoes the row
+    }
+  }
+  __syncthreads();
+  // the chunk's mask words: every row writes one contiguous run (up to 1 KiB)
+  const int w_first = c.t_begin >> 5;
+  for (int i = tid; i < 64 * n_tiles; i += kThreads) {
+    const int nl = i / n_tiles, w = i - nl * n_tiles;
+    const int r = E->row[nl];
+    if (r >= 0) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = E->mwords[nl][w];
+  }
 }
 
 template <int DK>
@@ -699,9 +699,8 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
     }
     E.astar[tid] = a;
     E.row[tid] = r;
-    E.ccnt[tid] = 0;
   }
-  for (int i = tid; i < 64 * (kWaves * kRoundTiles + 1); i += kThreads) (&E.mwords[0][0])[i] = 0u;
+  for (int i = tid; i < 64 * (kMaxChunkWords + 1); i += kThreads) (&E.mwords[0][0])[i] = 0u;
   __syncthreads();
   if (c.n0 + 32 < tab.NQ)
     emit_body<DK, true>(tab, c, I, tiles[wave], &E);
@@ -715,11 +714,6 @@ __global__ __launch_bounds__(256) void resolve_kernel(const FastTable tab) {
   RowInfo *info = tab.info + grow;
   const int tid = threadIdx.x;
   if (info->flag) return;
-  const int cnt = tab.cand_cnt[grow];
-  if (cnt > kCandCap) {
-    if (tid == 0) info->flag = 1;
-    return;
-  }
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const FastItem I = tab.it[it];
   __shared__ unsigned long long key[kCandCap];
@@ -728,13 +722,30 @@ __global__ __launch_bounds__(256) void resolve_kernel(const FastTable tab) {
   __shared__ int hcnt[256];
   __shared__ unsigned long long sh_prefix;
   __shared__ double sh_above;
+  __shared__ int sh_total;
+  if (tid == 0) sh_total = 0;
+  __syncthreads();
   const float ref = info->mdot * tab.c2;
-  const uint2 *src = tab.cands + (size_t)grow * kCandCap;
-  for (int i = tid; i < cnt; i += 256) {
-    const uint2 e = src[i];
-    const float d = __uint_as_float(e.x);
-    key[i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-    wgt[i] = exp2f(fmaf(d, tab.c2, -ref));
+  // gather the row's sub-lists (order is irrelevant: keys are unique)
+  const int n_sub = I.n_chunks * 2 * kWaves;
+  for (int sub = tid; sub < n_sub; sub += 256) {
+    const int n = tab.cand_cnt[(size_t)grow * tab.sub_per_row + sub];
+    if (n > 0) {
+      const int off = atomicAdd(&sh_total, n);
+      const uint2 *src = tab.cands + ((size_t)grow * tab.sub_per_row + sub) * kSubCap;
+      for (int i = 0; i < n && off + i < kCandCap; ++i) {
+        const uint2 e = src[i];
+        const float d = __uint_as_float(e.x);
+        key[off + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
+        wgt[off + i] = exp2f(fmaf(d, tab.c2, -ref));
+      }
+    }
+  }
+  __syncthreads();
+  const int cnt = sh_total;
+  if (cnt > kCandCap) {
+    if (tid == 0) info->flag = 1;
+    return;
   }
   if (tid == 0) { sh_prefix = 0ull; sh_above = info->above; }
   const double target = info->target;
@@ -769,7 +780,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(const FastTable tab) {
   for (int i = tid; i < cnt; i += 256) {
     if (key[i] >= tau) {
       const uint32_t t = 0xFFFFFFFFu - (uint32_t)(key[i] & 0xFFFFFFFFull);
-      atomicOr(&mrow[t >> 5], 1u << (t & 31));
+      if (t < (uint32_t)I.L) atomicOr(&mrow[t >> 5], 1u << (t & 31));
     }
   }
 }
@@ -796,12 +807,14 @@ bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p) {
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S) {
   FastPlan pl;
   const int NQ = S * (sh->n_q_heads / sh->n_kv_heads);
-  size_t max_slots = 0, max_rows = 0, max_tiles = 0;
+  size_t max_slots = 0, max_rows = 0, max_tiles = 0, max_sub = 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
     const int ck = pick_chunk_keys(sh, items + b0, nb);
     size_t slots = 0, tiles = 0;
     for (int i = 0; i < nb; ++i) {
+      const size_t sub = (size_t)ceil_div(items[b0 + i].L, ck) * 2 * kWaves;
+      if (sub > max_sub) max_sub = sub;
       slots += (size_t)sh->n_kv_heads * ceil_div(items[b0 + i].L, ck);
       tiles += (size_t)sh->n_kv_heads * ((items[b0 + i].L + 31) / 32);
     }
@@ -815,8 +828,8 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
   pl.off_hist = pl.off_top + align_up(max_slots * NQ * sizeof(int), 256);
   pl.off_info = pl.off_hist + align_up(max_slots * NQ * kBins * sizeof(float), 256);
   pl.off_cnt = pl.off_info + align_up(max_rows * sizeof(RowInfo), 256);
-  pl.off_cands = pl.off_cnt + align_up(max_rows * sizeof(int), 256);
-  pl.off_tmax = pl.off_cands + align_up(max_rows * kCandCap * sizeof(uint2), 256);
+  pl.off_cands = pl.off_cnt + align_up(max_rows * max_sub * sizeof(int), 256);
+  pl.off_tmax = pl.off_cands + align_up(max_rows * max_sub * kSubCap * sizeof(uint2), 256);
   pl.ws_bytes = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
   return pl;
 }
@@ -848,7 +861,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.info = reinterpret_cast<RowInfo *>(wsb + pl.off_info);
     tab.cand_cnt = reinterpret_cast<int *>(wsb + pl.off_cnt);
     tab.cands = reinterpret_cast<uint2 *>(wsb + pl.off_cands);
-    int wg = 0, part = 0;
+    int wg = 0, part = 0, most_chunks = 0;
     long long tmax0 = 0;
     for (int i = 0; i < nb; ++i) {
       const gvote_item &g = items[b0 + i];
@@ -856,12 +869,14 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       f.k = g.k; f.tok_stride = g.kv_tok_stride; f.head_stride = g.kv_head_stride;
       f.mask_off = mask_off; f.L = g.L; f.W = (g.L + 31) / 32;
       f.n_chunks = ceil_div(g.L, tab.chunk_keys);
+      if (f.n_chunks > most_chunks) most_chunks = f.n_chunks;
       f.wg0 = wg; f.part0 = part; f.pad = 0; f.tmax0 = tmax0;
       tmax0 += (long long)sh->n_kv_heads * f.W * tab.NQ;
       wg += sh->n_kv_heads * f.n_chunks * tab.NQB;
       part += sh->n_kv_heads * f.n_chunks;
       mask_off += (long long)tab.rows_per_item * f.W;
     }
+    tab.sub_per_row = most_chunks * 2 * kWaves; tab.pad0 = 0;
     const int rows = nb * tab.rows_per_item;
     if (sh->head_dim == 128) {
       hipLaunchKernelGGL(score_hist_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
