@@ -62,7 +62,8 @@ template <> struct Acc<float> { typedef double type; };
 // walking the 256 digit bins from 255 down, find the first non-empty digit at which `above` plus
 // the weights met so far reaches `target`; if rounding leaves the total short, take the lowest
 // non-empty digit.  Returns the digit; `above` becomes the weight strictly above it.
-__device__ __forceinline__ int pick_digit_wave(const float *hist, const int *cnt, double &above, double target,
+template <typename H>
+__device__ __forceinline__ int pick_digit_wave(const H *hist, const int *cnt, double &above, double target,
                                                int lane) {
   // lane 0 holds digits 255..252, lane 63 digits 3..0
   double h[4];

@@ -709,77 +709,110 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
 }
 
 // ------------------------------------------------------------------ per row: exact cut among the candidates
-__global__ __launch_bounds__(256) void resolve_kernel(const FastTable tab) {
-  const int grow = blockIdx.x;
+// One WAVE per row, no workgroup barrier: the row's candidates (the keys inside its cut bin, typically a
+// few dozen) are gathered from the sub-lists into wave-private LDS, then an 8-digit radix search over the
+// 64-bit key (ordered raw dot, ~position) finds the last key the target needs; weights are fixed point
+// relative to the cut bin's edge (integer LDS atomics).
+// Rows with at most 64 candidates (the usual case) need no search at all: with one candidate per lane,
+// 64 exchange steps give every lane the total weight of the keys ahead of its own; a key is needed iff
+// that weight still falls short of the target.  Launched twice: CAP = 256 for everybody, then CAP =
+// kCandCap for the rows the first launch marked as larger (flag 2); rows beyond kCandCap get flag 1.
+constexpr int kResolveWaves = 4;
+template <int CAP>
+struct ResolveLds {
+  unsigned long long key[CAP];
+  uint32_t wgt[CAP];
+  uint32_t hist[256];
+  int hcnt[256];
+};
+
+template <int CAP, bool SECOND>
+__global__ __launch_bounds__(kResolveWaves * 64) void resolve_kernel(const FastTable tab, int n_rows) {
+  __shared__ ResolveLds<CAP> lds[kResolveWaves];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int grow = blockIdx.x * kResolveWaves + wave;
+  if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
-  const int tid = threadIdx.x;
-  if (info->flag) return;
+  const int flag = info->flag;
+  if (SECOND ? flag != 2 : flag != 0) return;
+  ResolveLds<CAP> &M = lds[wave];
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const FastItem I = tab.it[it];
-  __shared__ unsigned long long key[kCandCap];
-  __shared__ float wgt[kCandCap];
-  __shared__ float hist[256];
-  __shared__ int hcnt[256];
-  __shared__ unsigned long long sh_prefix;
-  __shared__ double sh_above;
-  __shared__ int sh_total;
-  if (tid == 0) sh_total = 0;
-  __syncthreads();
-  const float ref = info->mdot * tab.c2;
-  // gather the row's sub-lists (order is irrelevant: keys are unique)
+  // fixed-point scale: weights relative to the upper edge of the cut bin, 2^kFixBits each at most
+  const double edge = (double)(info->astar + 1) * (double)kLog2ePerBin;       // log2 units
+  const float efix = (float)((double)kFixBits - edge);
+  const double unit = exp2((double)info->mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);
+  const double target = info->target * unit;
+  double above = info->above * unit;
+
+  // gather the sub-lists (order is irrelevant: keys are unique)
   const int n_sub = I.n_chunks * 2 * kWaves;
-  for (int sub = tid; sub < n_sub; sub += 256) {
-    const int n = tab.cand_cnt[(size_t)grow * tab.sub_per_row + sub];
-    if (n > 0) {
-      const int off = atomicAdd(&sh_total, n);
-      const uint2 *src = tab.cands + ((size_t)grow * tab.sub_per_row + sub) * kSubCap;
-      for (int i = 0; i < n && off + i < kCandCap; ++i) {
+  int cnt = 0;
+  for (int s0 = 0; s0 < n_sub; s0 += 64) {
+    const int sub = s0 + lane;
+    const int n = sub < n_sub ? tab.cand_cnt[(size_t)grow * tab.sub_per_row + sub] : 0;
+    int x = n;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int y = __shfl_up(x, off, 64);
+      if (lane >= off) x += y;
+    }
+    const int dst0 = cnt + x - n;
+    const uint2 *src = tab.cands + ((size_t)grow * tab.sub_per_row + sub) * kSubCap;
+    for (int i = 0; i < n; ++i) {
+      if (dst0 + i < CAP) {
         const uint2 e = src[i];
         const float d = __uint_as_float(e.x);
-        key[off + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-        wgt[off + i] = exp2f(fmaf(d, tab.c2, -ref));
+        M.key[dst0 + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
+        M.wgt[dst0 + i] = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
       }
     }
+    cnt += __shfl(x, 63, 64);
   }
-  __syncthreads();
-  const int cnt = sh_total;
-  if (cnt > kCandCap) {
-    if (tid == 0) info->flag = 1;
+  if (cnt > CAP) {
+    if (lane == 0) info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 1;
     return;
   }
-  if (tid == 0) { sh_prefix = 0ull; sh_above = info->above; }
-  const double target = info->target;
-  __syncthreads();
+  if (SECOND && lane == 0) info->flag = 0;
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  uint32_t *mrow = tab.rowmask + I.mask_off + (long long)r * I.W;
+  if (cnt <= 64) {
+    const bool have = lane < cnt;
+    const unsigned long long mykey = have ? M.key[lane] : 0ull;
+    const uint32_t myw = have ? M.wgt[lane] : 0u;
+    unsigned long long ahead = 0ull;       // fixed-point weight of the candidates ranked before mine
+    for (int j = 0; j < cnt; ++j) {
+      const unsigned long long kj = __shfl(mykey, j, 64);
+      const uint32_t wj = __shfl(myw, j, 64);
+      if (kj > mykey) ahead += wj;
+    }
+    if (have && above + (double)ahead < target) {
+      const uint32_t t = 0xFFFFFFFFu - (uint32_t)(mykey & 0xFFFFFFFFull);
+      if (t < (uint32_t)I.L) atomicOr(&mrow[t >> 5], 1u << (t & 31));
+    }
+    return;
+  }
+  unsigned long long prefix = 0ull;
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
-    hist[tid] = 0.f;
-    hcnt[tid] = 0;
-    __syncthreads();
-    const unsigned long long prefix = sh_prefix;
-    for (int i = tid; i < cnt; i += 256) {
-      const unsigned long long k = key[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { M.hist[lane * 4 + i] = 0u; M.hcnt[lane * 4 + i] = 0; }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    for (int i = lane; i < cnt; i += 64) {
+      const unsigned long long k = M.key[i];
       if (pass == 0 || (k >> (shift + 8)) == prefix) {
         const int dg = (int)((k >> shift) & 255ull);
-        atomicAdd(&hist[dg], wgt[i]);
-        atomicAdd(&hcnt[dg], 1);
+        atomicAdd(&M.hist[dg], M.wgt[i]);
+        atomicAdd(&M.hcnt[dg], 1);
       }
     }
-    __syncthreads();
-    if (tid < 64) {
-      double above = sh_above;
-      const int pick = pick_digit_wave(hist, hcnt, above, target, tid);
-      if (tid == 0) {
-        sh_prefix = (prefix << 8) | (unsigned long long)pick;
-        sh_above = above;
-      }
-    }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    const int pick = pick_digit_wave(M.hist, M.hcnt, above, target, lane);
+    prefix = (prefix << 8) | (unsigned long long)(pick & 255);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
   }
-  const unsigned long long tau = sh_prefix;
-  uint32_t *mrow = tab.rowmask + I.mask_off + (long long)r * I.W;
-  for (int i = tid; i < cnt; i += 256) {
-    if (key[i] >= tau) {
-      const uint32_t t = 0xFFFFFFFFu - (uint32_t)(key[i] & 0xFFFFFFFFull);
+  for (int i = lane; i < cnt; i += 64) {
+    if (M.key[i] >= prefix) {
+      const uint32_t t = 0xFFFFFFFFu - (uint32_t)(M.key[i] & 0xFFFFFFFFull);
       if (t < (uint32_t)I.L) atomicOr(&mrow[t >> 5], 1u << (t & 31));
     }
   }
@@ -892,7 +925,11 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       hipLaunchKernelGGL(score_emit_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();
-    hipLaunchKernelGGL(resolve_kernel, dim3(rows), dim3(256), 0, st, tab);
+    hipLaunchKernelGGL((resolve_kernel<256, false>), dim3(ceil_div(rows, kResolveWaves)), dim3(kResolveWaves * 64), 0, st,
+                       tab, rows);
+    GVOTE_CHECK_LAUNCH();
+    hipLaunchKernelGGL((resolve_kernel<kCandCap, true>), dim3(ceil_div(rows, kResolveWaves)), dim3(kResolveWaves * 64), 0,
+                       st, tab, rows);
     GVOTE_CHECK_LAUNCH();
     // rows the histogram could not settle are redone exactly
     gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, GVOTE_SELECT_TOPP, nullptr, rowmask,

@@ -259,6 +259,13 @@ def test_select_bf16_fallbacks_and_ties(g):
     for p in (0.5, 0.95):
         gm, _ = _select_case(g, wl, [dict(it, k=kd)], q, p)
         assert U.check_rowmask_sandwich(gm, lg, U.p32(p), stol) <= 8
+    # flatter attention: hundreds of keys share the cut bin (the larger candidate paths of the resolver)
+    for scale in (0.25, 0.05):
+        ks = (it["k"].to(torch.float32) * scale).to(it["k"].dtype)
+        lg = O.scores(ref["q_tilde"], U.f32np(ks))
+        gm, _ = _select_case(g, wl, [dict(it, k=ks)], q, 0.9)
+        nb = U.check_rowmask_sandwich(gm, lg, U.p32(0.9), stol)
+        say("  key scale", scale, "boundary", nb, "mean row size", gm.sum(-1).mean())
     # a tiny p: only the arg-max key of each row
     gm, _ = _select_case(g, wl, [it], q, 1e-6)
     assert np.all(gm.sum(-1) == 1)
