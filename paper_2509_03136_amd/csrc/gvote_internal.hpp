@@ -179,8 +179,8 @@ struct ScoreTable {
   const int *k_per_row;                // call-indexed or null
   uint32_t *rowmask;
   float *row_max, *row_sum;            // call-indexed or null
-  const int *flags;                    // null, or one int per batch row (stride flag_stride): 0 = skip the row
-  int flag_stride, pad3;
+  const int *row_list;                 // null (every row of the batch), or the batch rows to process ...
+  const int *n_list;                   // ... and how many there are (device side)
   int *n_fallback;                     // null, or counter incremented once per row this kernel processes
   ScoreItem it[kMaxItems];
 };
@@ -224,20 +224,22 @@ struct FastTable {
   float *tile_max;          // per (item, KV head, 32-key tile, row): maximum raw dot, written by pass 1
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
+  int *n_list;              // rows of this batch waiting for the general selector (second word) ...
+  int *row_list;            // ... and their batch row indices
   int *cand_cnt;            // [rows][sub_per_row]: entries in each sub-list
   uint2 *cands;             // [rows][sub_per_row][kSubCap]: (raw dot bits, position)
   FastItem it[kMaxItems];
 };
-struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, ws_bytes; };
+struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, off_list, ws_bytes; };
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                float p, uint32_t *rowmask, float *row_max, float *row_sum, void *ws, hipStream_t st);
-// the exact general selector on a batch of <= kMaxItems items; with `flags` only rows whose flag is set
+// the exact general selector on a batch of <= kMaxItems items; with `row_list` only the listed rows
 gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
                                         const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
-                                        long long mask_off0, float *row_max, float *row_sum, const int *flags,
-                                        int flag_stride, int *n_fallback, hipStream_t st);
+                                        long long mask_off0, float *row_max, float *row_sum, const int *row_list,
+                                        const int *n_list, int *n_fallback, hipStream_t st);
 ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                  float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,

@@ -518,7 +518,10 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
     info->target = target;
   }
   if (j == 0) {
-    if (grow == 0 && tab.item0 == 0) *tab.n_fallback = 0;
+    if (grow == 0) {
+      if (tab.item0 == 0) *tab.n_fallback = 0;
+      *tab.n_list = 0;
+    }
     const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
     if (tab.row_max) tab.row_max[gr] = m * tab.scale;
     if (tab.row_sum) tab.row_sum[gr] = (float)Z;
@@ -734,6 +737,10 @@ __global__ __launch_bounds__(kResolveWaves * 64) void resolve_kernel(const FastT
   if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
   const int flag = info->flag;
+  if (SECOND && flag == 1) {            // settled as "needs the exact selector": queue the row
+    if (lane == 0) tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+    return;
+  }
   if (SECOND ? flag != 2 : flag != 0) return;
   ResolveLds<CAP> &M = lds[wave];
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
@@ -769,7 +776,10 @@ __global__ __launch_bounds__(kResolveWaves * 64) void resolve_kernel(const FastT
     cnt += __shfl(x, 63, 64);
   }
   if (cnt > CAP) {
-    if (lane == 0) info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 1;
+    if (lane == 0) {
+      info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 1;
+      if (SECOND) tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+    }
     return;
   }
   if (SECOND && lane == 0) info->flag = 0;
@@ -863,7 +873,8 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
   pl.off_cnt = pl.off_info + align_up(max_rows * sizeof(RowInfo), 256);
   pl.off_cands = pl.off_cnt + align_up(max_rows * max_sub * sizeof(int), 256);
   pl.off_tmax = pl.off_cands + align_up(max_rows * max_sub * kSubCap * sizeof(uint2), 256);
-  pl.ws_bytes = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
+  pl.off_list = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
+  pl.ws_bytes = pl.off_list + align_up(max_rows * sizeof(int), 256);
   return pl;
 }
 
@@ -887,6 +898,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.p = p;
     tab.q = q; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
+    tab.n_list = reinterpret_cast<int *>(wsb) + 1;
+    tab.row_list = reinterpret_cast<int *>(wsb + pl.off_list);
     tab.part_max = reinterpret_cast<float *>(wsb + pl.off_max);
     tab.part_top = reinterpret_cast<int *>(wsb + pl.off_top);
     tab.tile_max = reinterpret_cast<float *>(wsb + pl.off_tmax);
@@ -933,8 +946,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     GVOTE_CHECK_LAUNCH();
     // rows the histogram could not settle are redone exactly
     gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, GVOTE_SELECT_TOPP, nullptr, rowmask,
-                                                  batch_mask_off0, row_max, row_sum, &tab.info[0].flag,
-                                                  (int)(sizeof(RowInfo) / sizeof(int)), tab.n_fallback, st);
+                                                  batch_mask_off0, row_max, row_sum, tab.row_list, tab.n_list,
+                                                  tab.n_fallback, st);
     if (stt != GVOTE_OK) return stt;
   }
   return GVOTE_OK;

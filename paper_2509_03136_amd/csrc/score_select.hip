@@ -21,7 +21,7 @@ namespace gvote {
 
 namespace {
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 1024;
 
 // fp32 -> uint32 that sorts like the float
 __device__ __forceinline__ uint32_t ordered_bits(float f) {
@@ -32,11 +32,13 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u) {
   return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
 }
 
+// weights in 2^-40 units of the row maximum's weight (integer LDS atomics; float ones run ~30x slower)
+constexpr double kSelFix = 1099511627776.0;
+
 template <typename T>
-__global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTable tab) {
+__device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow) {
   constexpr int NV = Vec16<T>::N;
-  const int grow = blockIdx.x;
-  if (tab.flags && tab.flags[(size_t)grow * tab.flag_stride] == 0) return;
+  constexpr int NW = kSelThreads / 64;
   const int it = grow / tab.rows_per_item;
   const int r = grow - it * tab.rows_per_item;
   const int s = r / tab.n_q_heads, h = r - s * tab.n_q_heads;
@@ -48,10 +50,11 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
   const bool topk = tab.mode == GVOTE_SELECT_TOPK;
 
   __shared__ float q_s[256];
-  __shared__ float hist[256];
+  __shared__ float lg[kSelThreads];          // logits of the current tile of kSelThreads keys
+  __shared__ unsigned long long hist[256];
   __shared__ int cnt[256];
-  __shared__ float red_f[4];
-  __shared__ int red_i[4];
+  __shared__ float red_f[NW];
+  __shared__ int red_i[NW];
   __shared__ uint32_t sh_prefix;
   __shared__ double sh_above, sh_target, sh_z;
   __shared__ int sh_ties, sh_take, sh_tie_base;
@@ -68,48 +71,69 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
   const T *kbase = reinterpret_cast<const T *>(I.k) + (long long)kvh * I.head_stride;
   typedef typename Acc<T>::type acc_t;
   const acc_t scale = (acc_t)tab.scale;
-  auto logit = [&](int t) -> float {
-    const T *kp = kbase + (long long)t * I.tok_stride;
-    acc_t acc = 0;
-    for (int c = 0; c < dk; c += NV) {
-      float kv[NV];
-      Vec16<T>::load(kp + c, kv);
+  // A key row is read by `lpk` neighbouring lanes, 16 bytes each (coalesced), the partial dot products
+  // are added across those lanes; every pass forms a key's logit by this very sequence.
+  const int ppr = dk / NV;                    // 16-byte pieces of a key row
+  int lpk = 1;
+  while (lpk < ppr) lpk <<= 1;                // lanes per key: power of two, <= 32
+  const int kpi = kSelThreads / lpk;          // keys per sweep of the workgroup
+  const int slot = tid / lpk, piece = tid - slot * lpk;
+  auto fill_tile = [&](int tile0) {           // lg[i] = logit of key tile0 + i, i < kSelThreads
+    for (int k0 = 0; k0 < kSelThreads; k0 += kpi) {
+      const int t = tile0 + k0 + slot;
+      acc_t acc = 0;
+      if (piece < ppr && t < L) {
+        float kv[NV];
+        Vec16<T>::load(kbase + (long long)t * I.tok_stride + piece * NV, kv);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[c + i], (acc_t)kv[i], acc);
+        for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[piece * NV + i], (acc_t)kv[i], acc);
+      }
+      for (int off = lpk >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+      if (piece == 0) lg[k0 + slot] = (float)(acc * scale) + 0.0f;   // "+ 0": -0 becomes +0, one pattern per value
     }
-    return (float)(acc * scale) + 0.0f;   // "+ 0" turns -0 into +0 so equal logits have one bit pattern
   };
 
   // ---- pass 0: row maximum
   float m = -INFINITY;
-  for (int t = tid; t < L; t += kSelThreads) m = fmaxf(m, logit(t));
+  for (int tile0 = 0; tile0 < L; tile0 += kSelThreads) {
+    fill_tile(tile0);
+    __syncthreads();
+    if (tile0 + tid < L) m = fmaxf(m, lg[tid]);
+    __syncthreads();
+  }
   for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
   if (lane == 0) red_f[wave] = m;
   __syncthreads();
-  m = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
+  m = red_f[0];
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, red_f[w]);
   __syncthreads();
 
   const bool keep_all = !topk && tab.p >= 1.0f;
   const int n_pass = keep_all ? 1 : 4;
+  auto fixed_weight = [&](float l) -> unsigned long long {
+    return topk ? 1ull : (unsigned long long)((double)expf(l - m) * kSelFix);
+  };
 
   // ---- passes 1..4: weighted radix search for the threshold
   for (int pass = 0; pass < n_pass; ++pass) {
     const int shift = 24 - 8 * pass;
-    hist[tid] = 0.f;
-    cnt[tid] = 0;
+    if (tid < 256) { hist[tid] = 0ull; cnt[tid] = 0; }
     __syncthreads();
     const uint32_t prefix = sh_prefix;
-    for (int t = tid; t < L; t += kSelThreads) {
-      const float l = logit(t);
-      const uint32_t u = ordered_bits(l);
-      if (pass == 0 || (u >> (shift + 8)) == prefix) {
-        const float w = topk ? 1.0f : expf(l - m);
-        const int dg = (u >> shift) & 255;
-        atomicAdd(&hist[dg], w);
-        atomicAdd(&cnt[dg], 1);
+    for (int tile0 = 0; tile0 < L; tile0 += kSelThreads) {
+      fill_tile(tile0);
+      __syncthreads();
+      if (tile0 + tid < L) {
+        const float l = lg[tid];
+        const uint32_t u = ordered_bits(l);
+        if (pass == 0 || (u >> (shift + 8)) == prefix) {
+          const int dg = (u >> shift) & 255;
+          atomicAdd(&hist[dg], fixed_weight(l));
+          atomicAdd(&cnt[dg], 1);
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
     if (pass == 0 && tid == 0) {
       double z = 0.0;
       for (int dg = 255; dg >= 0; --dg) z += (double)hist[dg];
@@ -141,9 +165,9 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
   int take = 0, ties = 0;
   if (!keep_all) {
     if (tid == 0) {
-      const float w_tau = topk ? 1.0f : expf(from_ordered_bits(sh_prefix) - m);
+      const double w_tau = (double)fixed_weight(from_ordered_bits(sh_prefix));
       const double need = sh_target - sh_above;
-      int n = (int)ceil(need / (double)w_tau);
+      int n = w_tau > 0.0 ? (int)fmin(ceil(need / w_tau), 2.0e9) : sh_ties;
       n = n < 1 ? 1 : (n > sh_ties ? sh_ties : n);
       sh_take = n;
       sh_tie_base = 0;
@@ -156,41 +180,44 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
   if (tid == 0) {
     const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
     if (tab.row_max) tab.row_max[gr] = m;
-    if (tab.row_sum) tab.row_sum[gr] = (float)sh_z;
+    if (tab.row_sum) tab.row_sum[gr] = topk ? (float)sh_z : (float)(sh_z / kSelFix);
   }
 
-  // ---- pass 5: emit the row's bit mask, 256 keys per step, in position order
+  // ---- pass 5: emit the row's bit mask, kSelThreads keys per step, in position order
   uint32_t *mrow = tab.rowmask + I.mask_off + (long long)r * I.W;
   const int n_steps = (I.W * 32 + kSelThreads - 1) / kSelThreads;
   const bool rank_ties = !keep_all && take < ties;
   for (int step = 0; step < n_steps; ++step) {
     const int t = step * kSelThreads + tid;
+    if (!keep_all) {
+      fill_tile(step * kSelThreads);
+      __syncthreads();
+    }
     bool sel = false, tie = false;
     if (t < L) {
       if (keep_all) {
         sel = true;
       } else {
-        const uint32_t u = ordered_bits(logit(t));
+        const uint32_t u = ordered_bits(lg[tid]);
         sel = u > tau;
         tie = u == tau;
       }
     }
-    if (tie) {
-      if (!rank_ties) {
-        sel = true;
-      }
-    }
+    if (tie && !rank_ties) sel = true;
     if (rank_ties) {
       // position-ordered rank of this tie among all ties of the row
       const unsigned long long bal = __ballot(tie);
       const int before = __popcll(bal & ((1ull << lane) - 1ull));
       if (lane == 0) red_i[wave] = __popcll(bal);
       __syncthreads();
-      int base = sh_tie_base;
-      for (int w = 0; w < wave; ++w) base += red_i[w];
+      int base = sh_tie_base, all = 0;
+      for (int w = 0; w < NW; ++w) {
+        if (w < wave) base += red_i[w];
+        all += red_i[w];
+      }
       if (tie && base + before < take) sel = true;
       __syncthreads();
-      if (tid == 0) sh_tie_base += red_i[0] + red_i[1] + red_i[2] + red_i[3];
+      if (tid == 0) sh_tie_base += all;
     }
     const unsigned long long bits = __ballot(sel);
     const int w0 = (step * kSelThreads + wave * 64) >> 5;
@@ -198,7 +225,21 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTabl
       if (w0 < I.W) mrow[w0] = (uint32_t)bits;
       if (w0 + 1 < I.W) mrow[w0 + 1] = (uint32_t)(bits >> 32);
     }
-    if (rank_ties) __syncthreads();
+    __syncthreads();
+  }
+}
+
+// grid: every row of the batch (row_list null), or a fixed number of workgroups walking the list
+template <typename T>
+__global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTable tab) {
+  if (tab.row_list == nullptr) {
+    select_row_body<T>(tab, blockIdx.x);
+    return;
+  }
+  const int n = *tab.n_list;
+  for (int i = blockIdx.x; i < n; i += gridDim.x) {
+    select_row_body<T>(tab, tab.row_list[i]);
+    __syncthreads();
   }
 }
 
@@ -212,14 +253,14 @@ ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items
 
 gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
                                         const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
-                                        long long mask_off0, float *row_max, float *row_sum, const int *flags,
-                                        int flag_stride, int *n_fallback, hipStream_t st) {
+                                        long long mask_off0, float *row_max, float *row_sum, const int *row_list,
+                                        const int *n_list, int *n_fallback, hipStream_t st) {
   ScoreTable tab;
   tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
   tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = item0;
   tab.p = p; tab.pad2 = 0.f; tab.scale = 1.0 / sqrt((double)sh->head_dim);
   tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
-  tab.flags = flags; tab.flag_stride = flag_stride; tab.pad3 = 0; tab.n_fallback = n_fallback;
+  tab.row_list = row_list; tab.n_list = n_list; tab.n_fallback = n_fallback;
   long long mask_off = mask_off0;
   for (int i = 0; i < nb; ++i) {
     const gvote_item &g = items[i];
@@ -228,7 +269,8 @@ gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item 
     c.L = g.L; c.W = (g.L + 31) / 32; c.mask_off = mask_off; c.row0 = i * tab.rows_per_item; c.pad = 0;
     mask_off += (long long)tab.rows_per_item * c.W;
   }
-  const dim3 grid(nb * tab.rows_per_item);
+  const int all_rows = nb * tab.rows_per_item;
+  const dim3 grid(row_list ? (all_rows < 1024 ? all_rows : 1024) : all_rows);
   if (sh->dtype == GVOTE_F32)
     hipLaunchKernelGGL(select_row_kernel<float>, grid, dim3(kSelThreads), 0, st, tab);
   else
@@ -247,7 +289,7 @@ gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items,
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
     const gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, mode, k_per_row, rowmask,
-                                                        mask_off, row_max, row_sum, nullptr, 0, nullptr, st);
+                                                        mask_off, row_max, row_sum, nullptr, nullptr, nullptr, st);
     if (stt != GVOTE_OK) return stt;
     for (int i = 0; i < nb; ++i) mask_off += (long long)S * sh->n_q_heads * ((items[b0 + i].L + 31) / 32);
   }
