@@ -35,18 +35,12 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
   for (int i = 0; i < NV; ++i) { pivot[i] = 0.f; s[i] = 0.f; ss[i] = 0.f; }
   if (active) {
     Vec16<T>::load(base + (long long)r0 * I.stride, pivot);
-    for (int r = r0 + wave; r < r1; r += 4 * kFitUnroll) {
+    // main loop without any guard (straight-line loads keep all eight rows in flight), then a remainder
+    int r = r0 + wave;
+    for (; r + 4 * (kFitUnroll - 1) < r1; r += 4 * kFitUnroll) {
       float x[kFitUnroll][NV];
 #pragma unroll
-      for (int u = 0; u < kFitUnroll; ++u) {
-        const int rr = r + 4 * u;
-        if (rr < r1) {
-          Vec16<T>::load(base + (long long)rr * I.stride, x[u]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < NV; ++i) x[u][i] = pivot[i];
-        }
-      }
+      for (int u = 0; u < kFitUnroll; ++u) Vec16<T>::load(base + (long long)(r + 4 * u) * I.stride, x[u]);
 #pragma unroll
       for (int u = 0; u < kFitUnroll; ++u) {
 #pragma unroll
@@ -55,6 +49,16 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
           s[i] += dlt;
           ss[i] = fmaf(dlt, dlt, ss[i]);
         }
+      }
+    }
+    for (; r < r1; r += 4) {
+      float x[NV];
+      Vec16<T>::load(base + (long long)r * I.stride, x);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const float dlt = x[i] - pivot[i];
+        s[i] += dlt;
+        ss[i] = fmaf(dlt, dlt, ss[i]);
       }
     }
   }
