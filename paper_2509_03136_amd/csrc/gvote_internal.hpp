@@ -141,7 +141,8 @@ struct SampleItem {
   int pos0, n_future;
 };
 struct SampleTable {
-  int n_items, d, S, SP;          // SP: samples padded to a multiple of 32
+  int n_items, d, S, SP;          // SP: samples padded to a multiple of 32 (MFMA blocks)
+  int SPs, pad1;                  // SPs: samples padded to a multiple of 8: row pitch of the partial sums
   int n_out, head_dim, ksplits, kslice;
   float theta;
   int item0;                      // index of the batch's first item in the call (output offsets)
@@ -153,7 +154,7 @@ struct SampleTable {
   SampleItem it[kMaxItems];
 };
 struct SamplePlan {
-  int SP, ksplits, kslice;
+  int SP, SPs, ksplits, kslice;
   size_t h_bytes_per_item, partial_bytes_per_item, ws_bytes;
 };
 SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S);

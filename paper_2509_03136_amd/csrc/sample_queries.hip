@@ -105,10 +105,9 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hf = lane >> 5;
-  const int o = blockIdx.x * 128 + wave * 32 + col;
-  const bool o_ok = o < tab.n_out;
-  const bf16_t *wrow =
-      reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)(o_ok ? o : 0) * tab.d + k0 + hf * 32;
+  // rows beyond n_out re-read the last row (their products are never stored): no guard on the loads
+  const int o = min(blockIdx.x * 128 + wave * 32 + col, tab.n_out - 1);
+  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)o * tab.d + k0 + hf * 32;
   floatx16 acc[NSB];
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb)
@@ -116,17 +115,17 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
     for (int r = 0; r < 16; ++r) acc[sb][r] = 0.f;
 
   // one k-step = 64 channels: lane (row, hf) owns channels hf*32 .. hf*32+31 of its row, consumed
-  // 8 at a time by four MFMAs; the B operand uses the very same channel assignment.
-#pragma unroll 4
-  for (int kk = 0; kk < tab.kslice; kk += 64) {
-    bf16x8 a[4];
+  // 8 at a time by four MFMAs; the B operand uses the very same channel assignment.  Two k-steps of
+  // W_q are in flight ahead of the MFMAs.
+  auto load_a = [&](bf16x8(&a)[4], int kk) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int kp = kk + hf * 32 + i * 8;
       uint4 raw = make_uint4(0, 0, 0, 0);
-      if (o_ok && kp < klen) raw = *reinterpret_cast<const uint4 *>(wrow + kk + i * 8);
+      if (klen == tab.kslice || kk + hf * 32 + i * 8 < klen) raw = *reinterpret_cast<const uint4 *>(wrow + kk + i * 8);
       a[i] = __builtin_bit_cast(bf16x8, raw);
     }
+  };
+  auto mma = [&](const bf16x8(&a)[4], int kk) __attribute__((always_inline)) {
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
 #pragma unroll
@@ -135,17 +134,44 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
         acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], __builtin_bit_cast(bf16x8, raw), acc[sb], 0, 0, 0);
       }
     }
+  };
+  if (klen == tab.kslice) {          // full slice: straight-line loads
+    bf16x8 a0[4], a1[4];
+    {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a0[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + i * 8));
+    }
+    for (int kk = 0; kk < tab.kslice; kk += 128) {
+      if (kk + 64 < tab.kslice) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          a1[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + kk + 64 + i * 8));
+      }
+      mma(a0, kk);
+      if (kk + 128 < tab.kslice) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          a0[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + kk + 128 + i * 8));
+      }
+      if (kk + 64 < tab.kslice) mma(a1, kk + 64);
+    }
+  } else {                           // the last, shorter slice: guarded
+    for (int kk = 0; kk < tab.kslice; kk += 64) {
+      bf16x8 a[4];
+      load_a(a, kk);
+      mma(a, kk);
+    }
   }
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   // Rows are outputs o, columns are samples.
-  float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SP;
+  float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
   const int ob = blockIdx.x * 128 + wave * 32;
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int oo = ob + 8 * (r / 4) + 4 * hf + (r % 4);
-      if (oo < tab.n_out) part[(size_t)oo * tab.SP + sb * 32 + col] = acc[sb][r];
+      if (oo < tab.n_out && sb * 32 + col < tab.SPs) part[(size_t)oo * tab.SPs + sb * 32 + col] = acc[sb][r];
     }
   }
 }
@@ -160,8 +186,8 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const SampleTable 
   if (o >= tab.n_out) return;
   const T *wrow = reinterpret_cast<const T *>(tab.it[it].w_q) + (size_t)o * tab.d;
   const T *h = reinterpret_cast<const T *>(tab.h_tilde) + (size_t)it * tab.S * tab.d;
-  float *part = tab.partial + ((size_t)it * tab.n_out + o) * tab.SP;
-  for (int s0 = 0; s0 < tab.SP; s0 += 8) {
+  float *part = tab.partial + ((size_t)it * tab.n_out + o) * tab.SPs;
+  for (int s0 = 0; s0 < tab.SPs; s0 += 8) {
     typename Acc<T>::type acc[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc[u] = 0;
@@ -224,9 +250,9 @@ __global__ __launch_bounds__(256) void rope_finalize_kernel(const SampleTable ta
   for (int s = threadIdx.x & 31; s < tab.S; s += 32) {
     float a = 0.f, b = 0.f;
     for (int ks = 0; ks < tab.ksplits; ++ks) {
-      const float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SP;
-      a += part[(size_t)o1 * tab.SP + s];
-      b += part[(size_t)o2 * tab.SP + s];
+      const float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
+      a += part[(size_t)o1 * tab.SPs + s];
+      b += part[(size_t)o2 * tab.SPs + s];
     }
     a += b1;
     b += b2;
@@ -242,6 +268,7 @@ bool use_mfma(const gvote_shape *sh, int S) { return sh->dtype == GVOTE_BF16 && 
 SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S) {
   SamplePlan p;
   p.SP = (S + 31) / 32 * 32;
+  p.SPs = (S + 7) / 8 * 8;
   if (use_mfma(sh, S)) {
     // k-slices of 512 channels (a multiple of the 64-channel MFMA step); the last may be shorter
     p.kslice = sh->d_model < 512 ? (sh->d_model + 63) / 64 * 64 : 512;
@@ -253,7 +280,7 @@ SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S) {
   const int nb = n_items < kMaxItems ? n_items : kMaxItems;
   const size_t n_out = (size_t)sh->n_q_heads * sh->head_dim;
   p.h_bytes_per_item = align_up((size_t)S * sh->d_model * elem_bytes(sh->dtype), 256);
-  p.partial_bytes_per_item = (size_t)p.ksplits * n_out * p.SP * sizeof(float);
+  p.partial_bytes_per_item = (size_t)p.ksplits * n_out * p.SPs * sizeof(float);
   p.ws_bytes = nb * (p.h_bytes_per_item + p.partial_bytes_per_item);
   return p;
 }
@@ -266,7 +293,7 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
     SampleTable tab;
-    tab.n_items = nb; tab.d = sh->d_model; tab.S = S; tab.SP = plan.SP;
+    tab.n_items = nb; tab.d = sh->d_model; tab.S = S; tab.SP = plan.SP; tab.SPs = plan.SPs; tab.pad1 = 0;
     tab.n_out = n_out; tab.head_dim = sh->head_dim; tab.ksplits = plan.ksplits; tab.kslice = plan.kslice;
     tab.theta = sh->rope_theta; tab.item0 = b0;
     tab.mu = mu; tab.var = var;
