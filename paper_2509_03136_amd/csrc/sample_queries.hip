@@ -84,9 +84,10 @@ __global__ __launch_bounds__(256) void sample_hidden_kernel(const SampleTable ta
   }
 }
 
-// ---- bf16 MFMA projection.  grid (ceil(n_out/128), ksplits, items), 256 threads.
+// ---- bf16 MFMA projection.  grid (ceil(n_out/256), ksplits, items), 512 threads (8 waves x 32 outputs).
+constexpr int kProjWaves = 8;
 template <int NSB>
-__global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab) {
+__global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const SampleTable tab) {
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t *Bs = reinterpret_cast<bf16_t *>(smem);   // [32*NSB][kslice + 8]
   const int it = blockIdx.z, ks = blockIdx.y;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
   const int ldb = tab.kslice + 8;
   const bf16_t *hsrc = reinterpret_cast<const bf16_t *>(tab.h_tilde) + (size_t)it * tab.S * tab.d + k0;
   const int vec_per_row = tab.kslice / 8;
-  for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += 256) {
+  for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += kProjWaves * 64) {
     const int s = v / vec_per_row, kk = (v % vec_per_row) * 8;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (s < tab.S && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hf = lane >> 5;
   // rows beyond n_out re-read the last row (their products are never stored): no guard on the loads
-  const int o = min(blockIdx.x * 128 + wave * 32 + col, tab.n_out - 1);
+  const int o = min(blockIdx.x * (kProjWaves * 32) + wave * 32 + col, tab.n_out - 1);
   const bf16_t *wrow = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)o * tab.d + k0 + hf * 32;
   floatx16 acc[NSB];
 #pragma unroll
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(const SampleTable tab
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   // Rows are outputs o, columns are samples.
   float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
-  const int ob = blockIdx.x * 128 + wave * 32;
+  const int ob = blockIdx.x * (kProjWaves * 32) + wave * 32;
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
 #pragma unroll
@@ -316,7 +317,7 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
       hipLaunchKernelGGL(sample_hidden_kernel<bf16_t>, gs, dim3(256), 0, st, tab);
     GVOTE_CHECK_LAUNCH();
     if (mfma) {
-      const dim3 gp(ceil_div(n_out, 128), plan.ksplits, nb);
+      const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, nb);
       const int nsb = plan.SP / 32;
       const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t);
       if (nsb == 3)
@@ -326,13 +327,13 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 1)
-        hipLaunchKernelGGL(project_mfma_kernel<1>, gp, dim3(256), lds, st, tab);
+        hipLaunchKernelGGL(project_mfma_kernel<1>, gp, dim3(kProjWaves * 64), lds, st, tab);
       else if (nsb == 2)
-        hipLaunchKernelGGL(project_mfma_kernel<2>, gp, dim3(256), lds, st, tab);
+        hipLaunchKernelGGL(project_mfma_kernel<2>, gp, dim3(kProjWaves * 64), lds, st, tab);
       else if (nsb == 3)
-        hipLaunchKernelGGL(project_mfma_kernel<3>, gp, dim3(256), lds, st, tab);
+        hipLaunchKernelGGL(project_mfma_kernel<3>, gp, dim3(kProjWaves * 64), lds, st, tab);
       else
-        hipLaunchKernelGGL(project_mfma_kernel<4>, gp, dim3(256), lds, st, tab);
+        hipLaunchKernelGGL(project_mfma_kernel<4>, gp, dim3(kProjWaves * 64), lds, st, tab);
     } else {
       const dim3 gp(ceil_div(n_out, 4), nb);
       if (sh->dtype == GVOTE_F32)
