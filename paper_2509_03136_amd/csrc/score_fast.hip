@@ -130,16 +130,26 @@ struct Tile {
     }
   }
 
-  // coalesced fetch of keys t0 .. t0+31 of one KV head.  No branches (the compiler then counts the
-  // outstanding loads exactly and the two-tile prefetch really overlaps): positions at or beyond `end`
-  // re-read key end-1, their products are discarded by the caller's validity test.
+  // coalesced fetch of keys t0 .. t0+31 of one KV head.  No per-lane branches (the compiler then counts
+  // the outstanding loads exactly and the prefetch really overlaps).  A tile that lies wholly inside
+  // the chunk is addressed as (wave-uniform base) + (32-bit lane offset): no 64-bit vector arithmetic;
+  // in the last, ragged tile positions at or beyond `end` re-read key end-1, their products are
+  // discarded by the caller's validity test.
   __device__ __forceinline__ void fetch(u32x4 (&pre)[LOADS], const bf16_t *khead, long long tok_stride, int t0, int end,
                                         int lane) const {
     const int piece = lane % PPR, sub = lane / PPR;
+    if (t0 + 32 <= end) {        // wave-uniform
+      const char *tile = reinterpret_cast<const char *>(khead) + (long long)t0 * tok_stride * 2;
+      const uint32_t lane_off = (uint32_t)(sub * (int)tok_stride + piece * 8) * 2u;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-      const int t = min(t0 + j * RPL + sub, end - 1);
-      pre[j] = *reinterpret_cast<const u32x4 *>(khead + (long long)t * tok_stride + piece * 8);
+      for (int j = 0; j < LOADS; ++j)
+        pre[j] = *reinterpret_cast<const u32x4 *>(tile + (long long)(j * RPL) * tok_stride * 2 + lane_off);
+    } else {
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        const int t = min(t0 + j * RPL + sub, end - 1);
+        pre[j] = *reinterpret_cast<const u32x4 *>(khead + (long long)t * tok_stride + piece * 8);
+      }
     }
   }
 
