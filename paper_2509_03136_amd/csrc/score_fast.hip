@@ -78,6 +78,11 @@ __device__ __forceinline__ int lds_offset(const void *p) {
 #endif
 }
 
+// A tile nominally covers keys t0 .. t0+31 of the chunk ending at `end`; when that would run past the
+// end the 32 keys end-32 .. end-1 are loaded instead (every item has at least 32 keys) and the first
+// t0 - origin of them, which belong to the previous tile or chunk, are ignored.
+__device__ __forceinline__ int tile_origin(int t0, int end) { return min(t0, end - 32); }
+
 // position of accumulator register r of lane (hf = lane / 32) inside the 32-key tile
 __device__ __forceinline__ int key_of(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
@@ -130,27 +135,17 @@ struct Tile {
     }
   }
 
-  // coalesced fetch of keys t0 .. t0+31 of one KV head.  No per-lane branches (the compiler then counts
-  // the outstanding loads exactly and the prefetch really overlaps).  A tile that lies wholly inside
-  // the chunk is addressed as (wave-uniform base) + (32-bit lane offset): no 64-bit vector arithmetic;
-  // in the last, ragged tile positions at or beyond `end` re-read key end-1, their products are
-  // discarded by the caller's validity test.
-  __device__ __forceinline__ void fetch(u32x4 (&pre)[LOADS], const bf16_t *khead, long long tok_stride, int t0, int end,
+  // Coalesced fetch of the 32 keys t .. t+31 of one KV head, all of which must exist (callers pull a
+  // ragged last tile back to `end - 32`, see tile_origin).  Addresses are (wave-uniform base) + (32-bit
+  // lane offset) and nothing is conditional, so the loads of several tiles stay in flight together.
+  __device__ __forceinline__ void fetch(u32x4 (&pre)[LOADS], const bf16_t *khead, long long tok_stride, int t,
                                         int lane) const {
     const int piece = lane % PPR, sub = lane / PPR;
-    if (t0 + 32 <= end) {        // wave-uniform
-      const char *tile = reinterpret_cast<const char *>(khead) + (long long)t0 * tok_stride * 2;
-      const uint32_t lane_off = (uint32_t)(sub * (int)tok_stride + piece * 8) * 2u;
+    const char *tile = reinterpret_cast<const char *>(khead) + (long long)t * tok_stride * 2;
+    const uint32_t lane_off = (uint32_t)(sub * (int)tok_stride + piece * 8) * 2u;
 #pragma unroll
-      for (int j = 0; j < LOADS; ++j)
-        pre[j] = *reinterpret_cast<const u32x4 *>(tile + (long long)(j * RPL) * tok_stride * 2 + lane_off);
-    } else {
-#pragma unroll
-      for (int j = 0; j < LOADS; ++j) {
-        const int t = min(t0 + j * RPL + sub, end - 1);
-        pre[j] = *reinterpret_cast<const u32x4 *>(khead + (long long)t * tok_stride + piece * 8);
-      }
-    }
+    for (int j = 0; j < LOADS; ++j)
+      pre[j] = *reinterpret_cast<const u32x4 *>(tile + (long long)(j * RPL) * tok_stride * 2 + lane_off);
   }
 
   __device__ __forceinline__ void stage(const u32x4 (&pre)[LOADS], unsigned char *lds, int lane) const {
@@ -188,63 +183,6 @@ struct Tile {
   }
 };
 
-// The K stream of one wave: tiles wave, wave + 8, wave + 16, ... of the chunk [t_begin, t_end), with the
-// global loads of the next TWO tiles in flight (registers) while the current one is multiplied: with
-// 8 waves per CU that keeps 128 KiB per CU outstanding, what HBM latency needs at full bandwidth.
-// `epi(acc, t0)` consumes a tile's 32 x 64 products; `round_end(round)` runs after every kRoundTiles
-// tiles of every wave (all waves call it equally often, so it may hold workgroup barriers).
-template <int DK, bool TWO, class Epi, class RoundEnd>
-__device__ __forceinline__ void stream_tiles_impl(const Tile<DK> &T, unsigned char *lds, const bf16_t *khead,
-                                                  long long tok_stride, int t_begin, int t_end, int wave, int lane,
-                                                  Epi &&epi, RoundEnd &&round_end) {
-  constexpr int LOADS = Tile<DK>::LOADS;
-  const int n_tiles = (t_end - t_begin + 31) >> 5;
-  const int n_rounds = (n_tiles + kWaves * kRoundTiles - 1) / (kWaves * kRoundTiles);
-  u32x4 pa[LOADS], pb[LOADS];
-  // (positions are clamped inside fetch, so the first two fetches need no guard)
-  T.fetch(pa, khead, tok_stride, t_begin + wave * 32, t_end, lane);
-  T.fetch(pb, khead, tok_stride, t_begin + (wave + kWaves) * 32, t_end, lane);
-  for (int k = 0; k < n_rounds * kRoundTiles; k += 2) {
-    {
-      const int tile = wave + kWaves * k;
-      if (tile < n_tiles) {
-        const int t0 = t_begin + tile * 32;
-        T.stage(pa, lds, lane);
-        if (tile + 2 * kWaves < n_tiles) T.fetch(pa, khead, tok_stride, t0 + 2 * kWaves * 32, t_end, lane);
-        __builtin_amdgcn_wave_barrier();
-        floatx16 acc[2];
-        T.template compute<TWO>(acc, lds, lane);
-        __builtin_amdgcn_wave_barrier();
-        epi(acc, t0, k);
-      }
-    }
-    {
-      const int tile = wave + kWaves * (k + 1);
-      if (tile < n_tiles) {
-        const int t0 = t_begin + tile * 32;
-        T.stage(pb, lds, lane);
-        if (tile + 2 * kWaves < n_tiles) T.fetch(pb, khead, tok_stride, t0 + 2 * kWaves * 32, t_end, lane);
-        __builtin_amdgcn_wave_barrier();
-        floatx16 acc[2];
-        T.template compute<TWO>(acc, lds, lane);
-        __builtin_amdgcn_wave_barrier();
-        epi(acc, t0, k + 1);
-      }
-    }
-    if ((k + 2) % kRoundTiles == 0) round_end((k + 2) / kRoundTiles - 1);
-  }
-}
-
-template <int DK, class Epi, class RoundEnd>
-__device__ __forceinline__ void stream_tiles(const Tile<DK> &T, unsigned char *lds, const bf16_t *khead,
-                                             long long tok_stride, int t_begin, int t_end, int wave, int lane,
-                                             bool two, Epi &&epi, RoundEnd &&round_end) {
-  if (two)
-    stream_tiles_impl<DK, true>(T, lds, khead, tok_stride, t_begin, t_end, wave, lane, epi, round_end);
-  else
-    stream_tiles_impl<DK, false>(T, lds, khead, tok_stride, t_begin, t_end, wave, lane, epi, round_end);
-}
-
 // ------------------------------------------------------------------ pass 1: maxima + weight histograms, one K read
 // The row maximum is not known while the chunk streams by, so the 256-bin window of each row slides:
 // bins sit on the absolute grid a = floor(d * c1) and hold weights relative to their own upper edge,
@@ -276,6 +214,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
   T.load_q(tab, c.it, c.kvh, c.n0, lane);
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
   const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
+  const int last_tile = wave < n_tiles ? wave + kWaves * ((n_tiles - 1 - wave) / kWaves) : n_tiles - 1;
   const float c1 = tab.c1, c2 = tab.c2;
   const float ebias = (float)kFixBits - kLog2ePerBin;
   uint32_t *hrow[2] = {hist + col * (kBins + 1), hist + (32 + col) * (kBins + 1)};
@@ -327,16 +266,20 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
 
   auto tile_body = [&](u32x4(&pre)[LOADS], int tile) __attribute__((always_inline)) {
     const int t0 = c.t_begin + tile * 32;
+    const int skip = t0 - tile_origin(t0, c.t_end);      // leading keys of the loaded window that are not this tile's
     floatx16 acc[2];
     // looked at early so the LDS latency hides behind the MFMAs; an event that opens after this look is
     // joined at the next tile (its barrier waits for this wave, so the histogram stays put meanwhile)
     const int pend_seen = *pending;
     T.stage(pre, ldstile, lane);
-    if (tile + kWaves < n_tiles) T.fetch(pre, khead, I.tok_stride, t0 + kWaves * 32, c.t_end, lane);
+    {   // next tile of this wave (the last one is simply fetched again: no conditional load)
+      const int tn = c.t_begin + min(tile + kWaves, last_tile) * 32;
+      T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
+    }
     __builtin_amdgcn_wave_barrier();
     T.template compute<TWO>(acc, ldstile, lane);
     __builtin_amdgcn_wave_barrier();
-    // positions beyond the chunk repeat its last key (see fetch), so they cannot raise a maximum
+    // (keys ahead of a pulled-back tile are keys of the same row: they may enter the maxima, never the bins)
     float mx0 = acc[0][0], mx1 = acc[1][0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) { mx0 = fmaxf(mx0, acc[0][r]); mx1 = fmaxf(mx1, acc[1][r]); }
@@ -365,7 +308,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
     // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 18),
     // truncated (a uniform -2e-6 relative bias that cancels in every ratio of sums); LDS byte address
     // hrow + 4 (top - a), formed in fp32 (exact: all quantities are small integers).
-    if (t0 + 32 <= c.t_end) {
+    if (skip == 0) {
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         if (nb == 0 || TWO) {
@@ -393,7 +336,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
             const float d = acc[nb][r];
             const float af = fmaxf(floorf(d * c1), atail);
             const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
-            const uint32_t u = t0 + key_of(r, hf) < c.t_end ? (uint32_t)__builtin_amdgcn_exp2f(x) : 0u;
+            const uint32_t u = key_of(r, hf) >= skip ? (uint32_t)__builtin_amdgcn_exp2f(x) : 0u;
             lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
           }
         }
@@ -402,7 +345,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
   };
 
   u32x4 pa[LOADS];
-  T.fetch(pa, khead, I.tok_stride, c.t_begin + wave * 32, c.t_end, lane);
+  T.fetch(pa, khead, I.tok_stride, tile_origin(c.t_begin + min(wave, n_tiles - 1) * 32, c.t_end), lane);
   for (int tile = wave; tile < n_tiles; tile += kWaves) tile_body(pa, tile);
   if (lane < 32) {
     atomicMax(&S->rowmax[col], ordered_bits(mxrun[0]));
@@ -603,42 +546,34 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   auto process = [&](u32x4(&pre)[LOADS], int k, int k_refill) __attribute__((always_inline)) {
     const int tile = wave + kWaves * k;
     const int t0 = c.t_begin + tile * 32;
+    const int org = tile_origin(t0, c.t_end);
+    const int skip = t0 - org;          // leading keys of the loaded window that are not this tile's
     T.stage(pre, ldstile, lane);
-    if (k_refill >= 0) T.fetch(pre, khead, I.tok_stride, c.t_begin + (wave + kWaves * k_refill) * 32, c.t_end, lane);
+    {   // refill with the next tile to look at (or this one again: no conditional load)
+      const int tn = c.t_begin + (wave + kWaves * (k_refill >= 0 ? k_refill : k)) * 32;
+      T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
+    }
     __builtin_amdgcn_wave_barrier();
     floatx16 acc[2];
     T.template compute<TWO>(acc, ldstile, lane);
     __builtin_amdgcn_wave_barrier();
     // floor(d * c1) >= astar  <=>  d * c1 >= astar (astar is an integer): two compares, no floor
     uint32_t ge[2] = {0u, 0u}, gt[2] = {0u, 0u};
-    if (t0 + 32 <= c.t_end) {
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        if (nb == 0 || TWO) {
-          const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
+    for (int nb = 0; nb < 2; ++nb) {
+      if (nb == 0 || TWO) {
+        const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float x = acc[nb][r] * c1;
-            ge[nb] |= x >= lo ? (1u << key_of(r, hf)) : 0u;
-            gt[nb] |= x >= hi ? (1u << key_of(r, hf)) : 0u;
-          }
+        for (int r = 0; r < 16; ++r) {
+          const float x = acc[nb][r] * c1;
+          ge[nb] |= x >= lo ? (1u << key_of(r, hf)) : 0u;
+          gt[nb] |= x >= hi ? (1u << key_of(r, hf)) : 0u;
         }
       }
-    } else {
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        if (nb == 0 || TWO) {
-          const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key_of(r, hf);
-            const float x = acc[nb][r] * c1;
-            const bool valid = t0 + key < c.t_end;
-            ge[nb] |= (valid && x >= lo) ? (1u << key) : 0u;
-            gt[nb] |= (valid && x >= hi) ? (1u << key) : 0u;
-          }
-        }
-      }
+    }
+    if (skip) {                          // wave-uniform: a pulled-back last tile
+      const uint32_t mine = 0xFFFFFFFFu << skip;
+      ge[0] &= mine; ge[1] &= mine; gt[0] &= mine; gt[1] &= mine;
     }
     const uint32_t cm[2] = {ge[0] & ~gt[0], ge[1] & ~gt[1]};
     if (__any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
@@ -649,7 +584,7 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
           for (int r = 0; r < 16; ++r) {
             if (cm[nb] & (1u << key_of(r, hf))) {
               if (ccount[nb] < kSubCap)
-                cdst[nb][ccount[nb]] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(t0 + key_of(r, hf)));
+                cdst[nb][ccount[nb]] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(org + key_of(r, hf)));
               ++ccount[nb];
             }
           }
@@ -658,15 +593,17 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      const uint32_t w = gt[nb] | __shfl_xor(gt[nb], 32, 64);
+      const uint32_t w = (gt[nb] | __shfl_xor(gt[nb], 32, 64)) >> skip;   // bit i = key t0 + i
       if (lane < 32 && w != 0u) E->mwords[32 * nb + lane][tile] = w;
     }
   };
 
   u32x4 pa[LOADS], pb[LOADS];
   int ka = next_k(), kb = next_k();
-  if (ka >= 0) T.fetch(pa, khead, I.tok_stride, c.t_begin + (wave + kWaves * ka) * 32, c.t_end, lane);
-  if (kb >= 0) T.fetch(pb, khead, I.tok_stride, c.t_begin + (wave + kWaves * kb) * 32, c.t_end, lane);
+  if (ka >= 0) {
+    T.fetch(pa, khead, I.tok_stride, tile_origin(c.t_begin + (wave + kWaves * ka) * 32, c.t_end), lane);
+    T.fetch(pb, khead, I.tok_stride, tile_origin(c.t_begin + (wave + kWaves * (kb >= 0 ? kb : ka)) * 32, c.t_end), lane);
+  }
   while (ka >= 0) {
     const int ka2 = next_k();
     process(pa, ka, ka2);

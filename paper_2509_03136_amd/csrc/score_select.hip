@@ -283,8 +283,9 @@ gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items,
                                  float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
                                  float *row_sum, void *ws, size_t ws_bytes, hipStream_t st) {
   (void)ws_bytes;
-  if (fast_path_ok(sh, S, mode, p))
-    return launch_score_fast(sh, items, n_items, S, q, p, rowmask, row_max, row_sum, ws, st);
+  bool fast = fast_path_ok(sh, S, mode, p);
+  for (int i = 0; i < n_items && fast; ++i) fast = items[i].L >= 32;   // the matrix-core path loads whole 32-key tiles
+  if (fast) return launch_score_fast(sh, items, n_items, S, q, p, rowmask, row_max, row_sum, ws, st);
   long long mask_off = 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
