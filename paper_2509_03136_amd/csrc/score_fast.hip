@@ -577,15 +577,21 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     }
     const uint32_t cm[2] = {ge[0] & ~gt[0], ge[1] & ~gt[1]};
     if (__any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
+      // accumulator registers 4g .. 4g+3 hold four neighbouring keys: one wave-uniform test per group
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        if (cm[nb]) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            if (cm[nb] & (1u << key_of(r, hf))) {
-              if (ccount[nb] < kSubCap)
-                cdst[nb][ccount[nb]] = make_uint2(__float_as_uint(acc[nb][r]), (uint32_t)(org + key_of(r, hf)));
-              ++ccount[nb];
+        for (int g = 0; g < 4; ++g) {
+          const uint32_t grp = (cm[nb] >> (8 * g + 4 * hf)) & 0xFu;
+          if (__any(grp != 0u)) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if (grp & (1u << i)) {
+                if (ccount[nb] < kSubCap)
+                  cdst[nb][ccount[nb]] =
+                      make_uint2(__float_as_uint(acc[nb][4 * g + i]), (uint32_t)(org + 8 * g + 4 * hf + i));
+                ++ccount[nb];
+              }
             }
           }
         }
@@ -624,10 +630,12 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   __syncthreads();
   // the chunk's mask words: every row writes one contiguous run (up to 1 KiB)
   const int w_first = c.t_begin >> 5;
-  for (int i = tid; i < 64 * n_tiles; i += kThreads) {
-    const int nl = i / n_tiles, w = i - nl * n_tiles;
+  for (int nl = tid >> 3; nl < 64; nl += kThreads >> 3) {      // eight threads per row, 32-byte runs
     const int r = E->row[nl];
-    if (r >= 0) tab.rowmask[I.mask_off + (long long)r * I.W + w_first + w] = E->mwords[nl][w];
+    if (r >= 0) {
+      uint32_t *dst = tab.rowmask + I.mask_off + (long long)r * I.W + w_first;
+      for (int w = tid & 7; w < n_tiles; w += 8) dst[w] = E->mwords[nl][w];
+    }
   }
 }
 
