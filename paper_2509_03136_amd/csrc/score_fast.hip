@@ -400,15 +400,17 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
   for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
 }
 
-// ------------------------------------------------------------------ per row: bin of the cut.  grid = rows, 256 threads
-__global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
-  const int grow = blockIdx.x;
+// ------------------------------------------------------------------ per row: bin of the cut.  One wave per row.
+constexpr int kFindWaves = 4;
+__global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTable tab, int n_rows) {
+  const int lane = threadIdx.x & 63;
+  const int grow = blockIdx.x * kFindWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (grow >= n_rows) return;
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const int s = r / tab.Hq, h = r - s * tab.Hq;
   const int kvh = h / tab.G, g = h - kvh * tab.G;
   const int n = s * tab.G + g;
   const FastItem I = tab.it[it];
-  const int j = threadIdx.x, lane = j & 63, wave = j >> 6;
   const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
   float m = -INFINITY;
   int top = kTopUnset;
@@ -419,58 +421,62 @@ __global__ __launch_bounds__(kBins) void find_bin_kernel(const FastTable tab) {
   // Every chunk binned inside its own window; on the absolute grid its bin jl is global bin
   // jl + (top - top_chunk).  Weights are fixed-point sums relative to the bin's upper edge, so the
   // chunks' sums of one absolute bin simply add: mass = sum * 2^-kFixBits * exp2(edge - max) in log2
-  // units.  Chunk bins at or beyond the last global bin (and the chunks' own last bins) are gathered by
-  // thread kBins - 1.
+  // units.  Chunk bins at or beyond the last global bin (and the chunks' own last bins) all fall into
+  // the last global bin.  A lane owns bins lane, lane + 64, lane + 128, lane + 192.
   const double mref = (double)m * (double)tab.c2;
-  double mine = 0.0;
-  float tailpart = 0.f;    // this thread's share of the last global bin, relative to that bin's edge
-  {
-    unsigned long long acc = 0ull;
-    for (int ch = 0; ch < I.n_chunks; ++ch) {
-      const long long shift = (long long)top - (long long)tab.part_top[(slot0 + ch) * tab.NQ + n];
-      const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
-      const long long jl = (long long)j - shift;
-      if (j < kBins - 1 && jl >= 0) acc += hc[jl];
-      // chunk bin j of this chunk, if it lies at or beyond the last global bin
-      const long long over = (long long)j + shift - (kBins - 1);
-      if (over >= 0) {
-        const uint32_t u = hc[j];
-        if (u) tailpart += (float)u * __builtin_amdgcn_exp2f(-(float)over * kLog2ePerBin);
-      }
+  unsigned long long acc[4] = {0ull, 0ull, 0ull, 0ull};
+  float tailpart = 0.f;    // this lane's share of the last global bin, relative to that bin's edge
+  for (int ch = 0; ch < I.n_chunks; ++ch) {
+    const long long shift = (long long)top - (long long)tab.part_top[(slot0 + ch) * tab.NQ + n];
+    const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = lane + 64 * i;
+      const uint32_t u = hc[j];                       // chunk bin j
+      const long long gbin = (long long)j + shift;     // where it lands globally
+      if (gbin >= kBins - 1 && u)
+        tailpart += (float)u * __builtin_amdgcn_exp2f(-(float)(gbin - (kBins - 1)) * kLog2ePerBin);
+      const long long jl = (long long)j - shift;        // chunk bin that lands in my global bin j
+      if (j < kBins - 1 && jl >= 0) acc[i] += hc[jl];
     }
-    if (acc) mine = ldexp((double)acc, -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref);
   }
-  __shared__ float tsum[4];
   for (int off = 32; off > 0; off >>= 1) tailpart += __shfl_xor(tailpart, off, 64);
-  if (lane == 0) tsum[wave] = tailpart;
-  __syncthreads();
-  if (j == kBins - 1)
-    mine = ldexp((double)(tsum[0] + tsum[1] + tsum[2] + tsum[3]), -kFixBits) *
-           exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
-  // inclusive scan over bins (bin 0 = highest logits)
-  __shared__ double wsum[4];
-  double x = mine;
-  for (int off = 1; off < 64; off <<= 1) {
-    const double y = __shfl_up(x, off, 64);
-    if (lane >= off) x += y;
+  double mine[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = lane + 64 * i;
+    mine[i] = acc[i] ? ldexp((double)acc[i], -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0;
+    if (j == kBins - 1)
+      mine[i] = ldexp((double)tailpart, -kFixBits) * exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
   }
-  if (lane == 63) wsum[wave] = x;
-  __syncthreads();
-  double base = 0.0;
-  for (int w = 0; w < wave; ++w) base += wsum[w];
-  const double cum = base + x;
-  const double Z = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  // inclusive scan over bins (bin 0 = highest logits): within each group of 64 bins, then across groups
+  double cum[4], base = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    double x = mine[i];
+    for (int off = 1; off < 64; off <<= 1) {
+      const double y = __shfl_up(x, off, 64);
+      if (lane >= off) x += y;
+    }
+    cum[i] = base + x;
+    base += __shfl(x, 63, 64);
+  }
+  const double Z = base;
   const double target = (double)tab.p * Z;
-  const double before = cum - mine;
   RowInfo *info = tab.info + grow;
-  if (before < target && cum >= target) {
-    info->mdot = m;
-    info->astar = top - j;
-    info->flag = (j == kBins - 1) ? 1 : 0;
-    info->above = before;
-    info->target = target;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = lane + 64 * i;
+    const double before = cum[i] - mine[i];
+    if (before < target && cum[i] >= target) {
+      info->mdot = m;
+      info->astar = top - j;
+      info->flag = (j == kBins - 1) ? 1 : 0;
+      info->above = before;
+      info->target = target;
+    }
   }
-  if (j == 0) {
+  if (lane == 0) {
     if (grow == 0) {
       if (tab.item0 == 0) *tab.n_fallback = 0;
       *tab.n_list = 0;
@@ -882,13 +888,13 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     if (sh->head_dim == 128) {
       hipLaunchKernelGGL(score_hist_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(find_bin_kernel, dim3(rows), dim3(kBins), 0, st, tab);
+      hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_emit_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
     } else {
       hipLaunchKernelGGL(score_hist_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(find_bin_kernel, dim3(rows), dim3(kBins), 0, st, tab);
+      hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_emit_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
     }

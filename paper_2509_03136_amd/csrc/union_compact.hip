@@ -31,8 +31,19 @@ __global__ __launch_bounds__(256) void union_count_kernel(const UnionTable tab) 
   uint32_t acc = 0u;
   if (word < I.W) {
     const uint32_t *rm = tab.rowmask + I.rowmask_off + word;
-    for (int s = 0; s < tab.S; ++s)
-      for (int g = 0; g < G; ++g) acc |= rm[(long long)(s * tab.n_q_heads + kvh * G + g) * I.W];
+    // the S*G rows of the group, eight loads in flight at a time
+    const int n_rows = tab.S * G;
+    for (int i0 = 0; i0 < n_rows; i0 += 8) {
+      uint32_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = min(i0 + u, n_rows - 1);          // the last row is simply read again
+        const int s = i / G, g = i - s * G;
+        v[u] = rm[(long long)(s * tab.n_q_heads + kvh * G + g) * I.W];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc |= v[u];
+    }
     if (word == I.W - 1 && (I.L & 31)) acc &= (1u << (I.L & 31)) - 1u;   // never trust bits beyond L
     tab.union_mask[I.union_off + (long long)kvh * I.W + word] = acc;
   }
