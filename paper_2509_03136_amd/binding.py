@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libgvote.so")
+    """The in-tree library; GVOTE_LIB names another build of the same sources (kernel experiments)."""
+    return os.environ.get("GVOTE_LIB") or os.path.join(_HERE, "libgvote.so")
 
 
 class GVoteError(RuntimeError):

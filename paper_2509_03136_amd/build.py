@@ -12,14 +12,15 @@ LIB = os.path.join(HERE, "libgvote.so")
 SOURCES = ["gvote_api.cpp", "fit_gaussian.hip", "sample_queries.hip", "score_select.hip", "score_fast.hip", "union_compact.hip"]
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, out: str = LIB, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden", "-x", "hip",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-pass-failed", "-Wno-unused-command-line-argument",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+    cmd += list(extra)
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -28,7 +29,7 @@ def build(verbose: bool = True) -> str:
         print(out, flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

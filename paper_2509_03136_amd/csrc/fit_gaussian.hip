@@ -111,7 +111,7 @@ FitPlan plan_fit(const gvote_shape *sh, const gvote_item *items, int n_items) {
   for (int i = 0; i < n_items; ++i) rows += items[i].L - items[i].n_skip;
   const int nv = sh->dtype == GVOTE_F32 ? 4 : 8;
   const int colblocks = ceil_div(sh->d_model, 64 * nv);
-  int64_t rpc = (rows * colblocks + 4095) / 4096;
+  int64_t rpc = (rows * colblocks + 2047) / 2048;
   rpc = (rpc + 31) / 32 * 32;
   if (rpc < 64) rpc = 64;
   if (rpc > 4096) rpc = 4096;

@@ -27,6 +27,9 @@
 // x 32 query rows (kept in registers for the whole kernel), C[key][query row]: a lane owns ONE
 // query row and 16 keys, so row statistics need no cross-lane traffic inside the loop.
 #include "gvote_internal.hpp"
+#ifndef GVOTE_ABL
+#define GVOTE_ABL 0   // kernel-timing experiments only: 1 = no binning, 3 = also no maxima/events, 7 = also no MFMA
+#endif
 
 namespace gvote {
 
@@ -277,8 +280,18 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
       T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
     }
     __builtin_amdgcn_wave_barrier();
+#if (GVOTE_ABL & 4)
+    { const uint32_t gx = *reinterpret_cast<const uint32_t *>(ldstile + lane * 16);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { acc[0][r] = __uint_as_float(gx & 0x3FFFFFFFu); acc[1][r] = acc[0][r]; } }
+#else
     T.template compute<TWO>(acc, ldstile, lane);
+#endif
     __builtin_amdgcn_wave_barrier();
+#if (GVOTE_ABL & 2)
+    mxrun[0] = fmaxf(mxrun[0], acc[0][0] + acc[1][15]);
+    return;
+#endif
     // (keys ahead of a pulled-back tile are keys of the same row: they may enter the maxima, never the bins)
     float mx0 = acc[0][0], mx1 = acc[1][0];
 #pragma unroll
@@ -305,6 +318,9 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
       event = __builtin_amdgcn_readfirstlane(pend_seen) != 0;
     }
     if (event) sync_event();
+#if (GVOTE_ABL & 1)
+    return;
+#endif
     // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 18),
     // truncated (a uniform -2e-6 relative bias that cancels in every ratio of sums); LDS byte address
     // hrow + 4 (top - a), formed in fp32 (exact: all quantities are small integers).
