@@ -205,7 +205,7 @@ struct HistCtl {
   int pending, done, aborted, pad;
 };
 constexpr int kTopUnset = -(1 << 24);
-constexpr int kHeadroom = 2 * kBinsPerUnit;
+constexpr int kHeadroom = 4 * kBinsPerUnit;
 
 template <int DK, bool TWO>
 __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
@@ -236,11 +236,12 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
         const int newtop = amax + kHeadroom;
         uint32_t *h = hist + row * (kBins + 1);
         const long long sh = (long long)newtop - (long long)oldtop;
-        uint32_t v[4];
+        constexpr int BPL = kBins / 64;     // bins per lane
+        uint32_t v[BPL];
         float spill = 0.f;            // weight pushed past the window, re-referenced to the last bin's edge
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int j = lane * 4 + i;
+        for (int i = 0; i < BPL; ++i) {
+          const int j = lane * BPL + i;
           v[i] = h[j];
           const long long jn = j + sh;
           if (jn >= kBins - 1 && v[i] != 0u)
@@ -249,13 +250,18 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
         for (int off = 32; off > 0; off >>= 1) spill += __shfl_xor(spill, off, 64);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int j = lane * 4 + i;       // destination bin
+        for (int i = 0; i < BPL; ++i) {
+          const int j = lane * BPL + i;       // destination bin
           const long long src = j - sh;
           // all lanes take part in the exchange (a lane must be active to be read from)
-          const int si = (int)(src & 3);
-          const uint32_t pick = si == 0 ? v[0] : si == 1 ? v[1] : si == 2 ? v[2] : v[3];
-          const uint32_t got = __shfl(pick, src >= 0 ? (int)(src >> 2) : 0, 64);
+          // bin src lives in lane src / BPL at index src % BPL = (i - sh) mod BPL: the same index in every
+          // lane, so each lane offers that element and the reader only chooses the lane
+          const int sl = src >= 0 ? (int)(src / BPL) : 0;
+          const int si = (int)((((long long)i - sh) % BPL + BPL) % BPL);
+          uint32_t pick = v[0];
+#pragma unroll
+          for (int q = 1; q < BPL; ++q) pick = si == q ? v[q] : pick;
+          const uint32_t got = __shfl(pick, sl, 64);
           h[j] = j == kBins - 1 ? (uint32_t)(spill + 0.5f) : (src >= 0 ? got : 0u);
         }
         if (lane == 0) S->top[row] = newtop;
@@ -438,15 +444,18 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   // jl + (top - top_chunk).  Weights are fixed-point sums relative to the bin's upper edge, so the
   // chunks' sums of one absolute bin simply add: mass = sum * 2^-kFixBits * exp2(edge - max) in log2
   // units.  Chunk bins at or beyond the last global bin (and the chunks' own last bins) all fall into
-  // the last global bin.  A lane owns bins lane, lane + 64, lane + 128, lane + 192.
+  // the last global bin.  A lane owns bins lane, lane + 64, lane + 128, ...
   const double mref = (double)m * (double)tab.c2;
-  unsigned long long acc[4] = {0ull, 0ull, 0ull, 0ull};
+  constexpr int BPL = kBins / 64;     // bins per lane
+  unsigned long long acc[BPL];
+#pragma unroll
+  for (int i = 0; i < BPL; ++i) acc[i] = 0ull;
   float tailpart = 0.f;    // this lane's share of the last global bin, relative to that bin's edge
   for (int ch = 0; ch < I.n_chunks; ++ch) {
     const long long shift = (long long)top - (long long)tab.part_top[(slot0 + ch) * tab.NQ + n];
     const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < BPL; ++i) {
       const int j = lane + 64 * i;
       const uint32_t u = hc[j];                       // chunk bin j
       const long long gbin = (long long)j + shift;     // where it lands globally
@@ -457,18 +466,18 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     }
   }
   for (int off = 32; off > 0; off >>= 1) tailpart += __shfl_xor(tailpart, off, 64);
-  double mine[4];
+  double mine[BPL];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
     mine[i] = acc[i] ? ldexp((double)acc[i], -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0;
     if (j == kBins - 1)
       mine[i] = ldexp((double)tailpart, -kFixBits) * exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
   }
   // inclusive scan over bins (bin 0 = highest logits): within each group of 64 bins, then across groups
-  double cum[4], base = 0.0;
+  double cum[BPL], base = 0.0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < BPL; ++i) {
     double x = mine[i];
     for (int off = 1; off < 64; off <<= 1) {
       const double y = __shfl_up(x, off, 64);
@@ -481,7 +490,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   const double target = (double)tab.p * Z;
   RowInfo *info = tab.info + grow;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
     const double before = cum[i] - mine[i];
     if (before < target && cum[i] >= target) {
