@@ -565,6 +565,9 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) cdst[nb] = tab.cands + ((size_t)grow[nb] * tab.sub_per_row + sub) * kSubCap;
 
+#if (GVOTE_ABL & 32)
+  need = 0u;
+#endif
   uint32_t todo = need;        // tiles not yet fetched
   auto next_k = [&]() __attribute__((always_inline)) -> int {
     if (todo == 0u) return -1;
@@ -590,6 +593,9 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     __builtin_amdgcn_wave_barrier();
     // floor(d * c1) >= astar  <=>  d * c1 >= astar (astar is an integer): two compares, no floor
     uint32_t ge[2] = {0u, 0u}, gt[2] = {0u, 0u};
+#if (GVOTE_ABL & 16)
+    gt[0] = (acc[0][0] + acc[1][3]) == 12345.f ? 1u : 0u;
+#else
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       if (nb == 0 || TWO) {
@@ -602,12 +608,13 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
         }
       }
     }
+#endif
     if (skip) {                          // wave-uniform: a pulled-back last tile
       const uint32_t mine = 0xFFFFFFFFu << skip;
       ge[0] &= mine; ge[1] &= mine; gt[0] &= mine; gt[1] &= mine;
     }
     const uint32_t cm[2] = {ge[0] & ~gt[0], ge[1] & ~gt[1]};
-    if (__any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
+    if (!(GVOTE_ABL & 8) && __any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
       // accumulator registers 4g .. 4g+3 hold four neighbouring keys: one wave-uniform test per group
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
