@@ -144,7 +144,7 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
  * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
  * Diagnostic: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
- * of ws holds, after the call, the number of rows that had to be redone by the exact general selector
+ * of ws holds, after the call and until ws is used again, the number of rows that had to be redone by the exact general selector
  * (cut outside the histogram window, or too many keys tied around the cut). */
 GVOTE_API gvote_status gvote_score_select(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
                                 int32_t S, const void *q, float p, int32_t mode, const int32_t *k_per_row,

@@ -47,22 +47,42 @@ def oracle_item(wl, it, *, S=None, p=None, n_skip=None, pos0=None, n_future=1, b
     return out
 
 
-def sandwich(logits: np.ndarray, p: float, tol: float):
-    """Row masks of the oracle at p - tol, p, p + tol."""
-    lo = O.select_rows(logits, max(p - tol, 1e-9))
-    mid = O.select_rows(logits, p)
-    hi = O.select_rows(logits, min(p + tol, 1.0))
-    return lo, mid, hi
+def band_sets(logits_row: np.ndarray, p: float, tol: float):
+    """Keys a correct selection MUST hold and MAY hold, given that cumulative masses are only trusted to
+    `tol`.  In the oracle's order (logit descending, position ascending) key i occupies the cumulative-
+    mass interval (c_{i-1}, c_i] / Z.  Keys whose interval ends at or before p - tol must be selected;
+    keys whose interval starts at or after p + tol must not be; a key whose interval reaches into
+    [p - tol, p + tol] lies within the tolerance of the boundary and may go either way (two nearly tied
+    heavy keys may swap places when the logits carry bf16-level differences)."""
+    l = np.asarray(logits_row, dtype=np.float64)
+    _, w, Z = O.softmax_weights(l)
+    order = np.argsort(-l, kind="stable")
+    cum = np.cumsum(w[order])
+    must = np.zeros(l.shape[0], dtype=bool)
+    may = np.zeros(l.shape[0], dtype=bool)
+    must[order[cum <= (p - tol) * Z]] = True
+    may[order[(cum - w[order]) < (p + tol) * Z]] = True
+    if p >= 1.0:
+        must[:] = True
+        may[:] = True
+    return must, may
 
 
 def check_rowmask_sandwich(gpu_mask: np.ndarray, logits: np.ndarray, p: float, tol: float):
-    """gpu_mask bool [S, H_q, L].  Returns the number of boundary keys (gpu xor oracle-at-p)."""
-    lo, mid, hi = sandwich(logits, p, tol)
-    missing = lo & ~gpu_mask
-    extra = gpu_mask & ~hi
-    assert not missing.any(), f"{missing.sum()} keys of C(p - tol) are not selected"
-    assert not extra.any(), f"{extra.sum()} selected keys lie outside C(p + tol)"
-    return int((gpu_mask ^ mid).sum())
+    """gpu_mask bool [S, H_q, L]: must <= gpu <= may for every row.  Returns the number of boundary keys
+    (gpu xor the oracle's own selection at p)."""
+    S, hq, _ = logits.shape
+    boundary = 0
+    for s in range(S):
+        for h in range(hq):
+            must, may = band_sets(logits[s, h], p, tol)
+            got = gpu_mask[s, h]
+            missing, extra = must & ~got, got & ~may
+            assert not missing.any(), f"row ({s},{h}): {missing.sum()} keys entirely before the p - tol band are not selected"
+            assert not extra.any(), f"row ({s},{h}): {extra.sum()} selected keys lie entirely beyond the p + tol band"
+            assert got.any()
+            boundary += int((got ^ O.top_p_select(logits[s, h], p)).sum())
+    return boundary
 
 
 def unpack_rows(words: torch.Tensor, rows: int, L: int) -> np.ndarray:
