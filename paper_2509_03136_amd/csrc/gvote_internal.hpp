@@ -190,7 +190,7 @@ struct ScorePlan { size_t ws_bytes; };
 // bf16 fast path (score_fast.hip)
 constexpr int kBins = 256;            // histogram bins per row: 16 units of logit below the window top (the top sits up to 4 units above the maximum)
 constexpr int kBinsPerUnit = 16;      // bins per unit of logit: bin width 1/16, window 16 units
-constexpr int kCandCap = 1024;        // boundary-bin candidates a row may collect before it is redone exactly
+constexpr int kCandCap = 4096;        // boundary-bin candidates a row may collect before it is redone exactly
 constexpr int kSubCap = 16;           // entries of one candidate sub-list (row, key chunk, wave, lane half)
 struct RowInfo {
   float mdot;       // row maximum of the raw dot product

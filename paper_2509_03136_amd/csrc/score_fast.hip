@@ -711,9 +711,9 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
 // relative to the cut bin's edge (integer LDS atomics).
 // Rows with at most 64 candidates (the usual case) need no search at all: with one candidate per lane,
 // 64 exchange steps give every lane the total weight of the keys ahead of its own; a key is needed iff
-// that weight still falls short of the target.  Launched twice: CAP = 256 for everybody, then CAP =
-// kCandCap for the rows the first launch marked as larger (flag 2); rows beyond kCandCap get flag 1.
-constexpr int kResolveWaves = 4;
+// that weight still falls short of the target.  Launched twice: CAP = 256 for everybody (four rows per
+// workgroup), then CAP = kCandCap for the rows the first launch marked as larger (flag 2; one row per
+// workgroup); rows beyond kCandCap get flag 1.
 template <int CAP>
 struct ResolveLds {
   unsigned long long key[CAP];
@@ -723,7 +723,8 @@ struct ResolveLds {
 };
 
 template <int CAP, bool SECOND>
-__global__ __launch_bounds__(kResolveWaves * 64) void resolve_kernel(const FastTable tab, int n_rows) {
+__global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const FastTable tab, int n_rows) {
+  constexpr int kResolveWaves = SECOND ? 1 : 4;     // the large second tier needs the LDS of a whole workgroup
   __shared__ ResolveLds<CAP> lds[kResolveWaves];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int grow = blockIdx.x * kResolveWaves + wave;
@@ -931,11 +932,9 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       hipLaunchKernelGGL(score_emit_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();
-    hipLaunchKernelGGL((resolve_kernel<256, false>), dim3(ceil_div(rows, kResolveWaves)), dim3(kResolveWaves * 64), 0, st,
-                       tab, rows);
+    hipLaunchKernelGGL((resolve_kernel<256, false>), dim3(ceil_div(rows, 4)), dim3(256), 0, st, tab, rows);
     GVOTE_CHECK_LAUNCH();
-    hipLaunchKernelGGL((resolve_kernel<kCandCap, true>), dim3(ceil_div(rows, kResolveWaves)), dim3(kResolveWaves * 64), 0,
-                       st, tab, rows);
+    hipLaunchKernelGGL((resolve_kernel<kCandCap, true>), dim3(rows), dim3(64), 0, st, tab, rows);
     GVOTE_CHECK_LAUNCH();
     // rows the histogram could not settle are redone exactly
     gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, GVOTE_SELECT_TOPP, nullptr, rowmask,

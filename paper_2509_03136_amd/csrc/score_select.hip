@@ -79,17 +79,27 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
   const int kpi = kSelThreads / lpk;          // keys per sweep of the workgroup
   const int slot = tid / lpk, piece = tid - slot * lpk;
   auto fill_tile = [&](int tile0) {           // lg[i] = logit of key tile0 + i, i < kSelThreads
-    for (int k0 = 0; k0 < kSelThreads; k0 += kpi) {
-      const int t = tile0 + k0 + slot;
-      acc_t acc = 0;
-      if (piece < ppr && t < L) {
-        float kv[NV];
-        Vec16<T>::load(kbase + (long long)t * I.tok_stride + piece * NV, kv);
+    constexpr int UN = 8;                     // key rows in flight per lane
+    for (int k0 = 0; k0 < kSelThreads; k0 += UN * kpi) {
+      float kv[UN][NV];
 #pragma unroll
-        for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[piece * NV + i], (acc_t)kv[i], acc);
+      for (int u = 0; u < UN; ++u) {
+        const int t = tile0 + k0 + u * kpi + slot;
+        const int tc = t < L ? t : L - 1;     // in bounds; the result is dropped below
+        Vec16<T>::load(kbase + (long long)tc * I.tok_stride + (piece < ppr ? piece : 0) * NV, kv[u]);
       }
-      for (int off = lpk >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-      if (piece == 0) lg[k0 + slot] = (float)(acc * scale) + 0.0f;   // "+ 0": -0 becomes +0, one pattern per value
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        if (k0 + u * kpi < kSelThreads) {     // (only matters when a sweep covers more than 1/8 of the tile)
+          acc_t acc = 0;
+          if (piece < ppr) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[piece * NV + i], (acc_t)kv[u][i], acc);
+          }
+          for (int off = lpk >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+          if (piece == 0) lg[k0 + u * kpi + slot] = (float)(acc * scale) + 0.0f;   // "+ 0": -0 becomes +0
+        }
+      }
     }
   };
 
