@@ -219,6 +219,10 @@ class Pipeline:
         """Rows of the last select() redone by the exact general selector (matrix-core path only)."""
         return int(self.ws[:4].view(torch.int32).item())
 
+    def fallback_reasons(self):
+        """(cut below the histogram window, candidate sub-list overflow, too many candidates) row counts."""
+        return [int(x) for x in self.ws[8:20].view(torch.int32).tolist()]
+
     def compact(self):
         union_compact(self.b, self.S, self.rowmask, self.union_mask, self.budget, self.offsets, self.k_out,
                       self.v_out, self.idx_out, self.capacity, self.overflow, self.ws)

@@ -192,6 +192,7 @@ constexpr int kBins = 256;            // histogram bins per row: 16 units of log
 constexpr int kBinsPerUnit = 16;      // bins per unit of logit: bin width 1/16, window 16 units
 constexpr int kCandCap = 4096;        // boundary-bin candidates a row may collect before it is redone exactly
 constexpr int kSubCap = 16;           // entries of one candidate sub-list (row, key chunk, wave, lane half)
+constexpr int kOvfCap = 256;          // entries of a row's shared overflow list (for sub-lists that fill up)
 struct RowInfo {
   float mdot;       // row maximum of the raw dot product
   int astar;        // absolute bin index floor(dot * c1) in which the cut falls
@@ -229,9 +230,11 @@ struct FastTable {
   int *row_list;            // ... and their batch row indices
   int *cand_cnt;            // [rows][sub_per_row]: entries in each sub-list
   uint2 *cands;             // [rows][sub_per_row][kSubCap]: (raw dot bits, position)
+  int *ovf_cnt;             // [rows]: entries in the row's overflow list
+  uint2 *ovf;               // [rows][kOvfCap]
   FastItem it[kMaxItems];
 };
-struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, off_list, ws_bytes; };
+struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, off_list, off_ovfc, off_ovf, ws_bytes; };
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,

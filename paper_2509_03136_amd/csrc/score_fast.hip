@@ -496,14 +496,18 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     if (before < target && cum[i] >= target) {
       info->mdot = m;
       info->astar = top - j;
-      info->flag = (j == kBins - 1) ? 1 : 0;
+      info->flag = (j == kBins - 1) ? 1 : 0;      // 1: the cut lies below the histogram window
       info->above = before;
       info->target = target;
     }
   }
   if (lane == 0) {
+    tab.ovf_cnt[grow] = 0;
     if (grow == 0) {
-      if (tab.item0 == 0) *tab.n_fallback = 0;
+      if (tab.item0 == 0) {
+        *tab.n_fallback = 0;
+        tab.n_list[1] = 0; tab.n_list[2] = 0; tab.n_list[3] = 0;
+      }
       *tab.n_list = 0;
     }
     const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
@@ -625,9 +629,14 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               if (grp & (1u << i)) {
-                if (ccount[nb] < kSubCap)
-                  cdst[nb][ccount[nb]] =
-                      make_uint2(__float_as_uint(acc[nb][4 * g + i]), (uint32_t)(org + 8 * g + 4 * hf + i));
+                const uint2 e = make_uint2(__float_as_uint(acc[nb][4 * g + i]), (uint32_t)(org + 8 * g + 4 * hf + i));
+                if (ccount[nb] < kSubCap) {
+                  cdst[nb][ccount[nb]] = e;
+                } else {                       // rare: this lane's sub-list is full, use the row's shared list
+                  const int slot = atomicAdd(&tab.ovf_cnt[grow[nb]], 1);
+                  if (slot < kOvfCap) tab.ovf[(size_t)grow[nb] * kOvfCap + slot] = e;
+                  else tab.info[grow[nb]].flag = 3;   // 3: even the overflow list is full, the exact selector redoes the row
+                }
                 ++ccount[nb];
               }
             }
@@ -662,7 +671,6 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   for (int nb = 0; nb < 2; ++nb) {
     if ((nb == 0 || TWO) && c.n0 + 32 * nb + col < tab.NQ) {
       tab.cand_cnt[(size_t)grow[nb] * tab.sub_per_row + sub] = min(ccount[nb], kSubCap);
-      if (ccount[nb] > kSubCap) tab.info[grow[nb]].flag = 1;   // the exact selector redoes the row
     }
   }
   __syncthreads();
@@ -731,8 +739,11 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
   const int flag = info->flag;
-  if (SECOND && flag == 1) {            // settled as "needs the exact selector": queue the row
-    if (lane == 0) tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+  if (SECOND && (flag & 1)) {           // settled as "needs the exact selector": queue the row
+    if (lane == 0) {
+      tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+      atomicAdd(tab.n_list + 1 + (flag >> 1), 1);      // diagnostic: rows by reason (window, sub-list, capacity)
+    }
     return;
   }
   if (SECOND ? flag != 2 : flag != 0) return;
@@ -769,10 +780,25 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
     }
     cnt += __shfl(x, 63, 64);
   }
+  {   // the row's shared overflow list
+    const int n_ovf = min(tab.ovf_cnt[grow], kOvfCap);
+    for (int i = lane; i < n_ovf; i += 64) {
+      if (cnt + i < CAP) {
+        const uint2 e = tab.ovf[(size_t)grow * kOvfCap + i];
+        const float d = __uint_as_float(e.x);
+        M.key[cnt + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
+        M.wgt[cnt + i] = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
+      }
+    }
+    cnt += n_ovf;
+  }
   if (cnt > CAP) {
     if (lane == 0) {
-      info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 1;
-      if (SECOND) tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+      info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 5;   // 5: more candidates than the resolver holds
+      if (SECOND) {
+        tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
+        atomicAdd(tab.n_list + 3, 1);
+      }
     }
     return;
   }
@@ -868,7 +894,9 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
   pl.off_cands = pl.off_cnt + align_up(max_rows * max_sub * sizeof(int), 256);
   pl.off_tmax = pl.off_cands + align_up(max_rows * max_sub * kSubCap * sizeof(uint2), 256);
   pl.off_list = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
-  pl.ws_bytes = pl.off_list + align_up(max_rows * sizeof(int), 256);
+  pl.off_ovfc = pl.off_list + align_up(max_rows * sizeof(int), 256);
+  pl.off_ovf = pl.off_ovfc + align_up(max_rows * sizeof(int), 256);
+  pl.ws_bytes = pl.off_ovf + align_up(max_rows * kOvfCap * sizeof(uint2), 256);
   return pl;
 }
 
@@ -894,6 +922,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.n_list = reinterpret_cast<int *>(wsb) + 1;
     tab.row_list = reinterpret_cast<int *>(wsb + pl.off_list);
+    tab.ovf_cnt = reinterpret_cast<int *>(wsb + pl.off_ovfc);
+    tab.ovf = reinterpret_cast<uint2 *>(wsb + pl.off_ovf);
     tab.part_max = reinterpret_cast<float *>(wsb + pl.off_max);
     tab.part_top = reinterpret_cast<int *>(wsb + pl.off_top);
     tab.tile_max = reinterpret_cast<float *>(wsb + pl.off_tmax);
