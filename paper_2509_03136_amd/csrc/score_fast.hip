@@ -93,6 +93,20 @@ struct WgCoord {
   int it, kvh, chunk, qb, n0, t_begin, t_end, slot;
 };
 
+// Workgroup ids go round-robin over the 8 XCDs (each with its own L2).  When a KV group has more than
+// 64 query rows, its NQB row blocks all stream the same keys: the launch order is permuted so that the
+// NQB workgroups of one (head, chunk) slot get ids 8 apart, i.e. land on the same XCD close in time and
+// share the chunk through that XCD's L2.  Returns false for the padding ids of the last group.
+__device__ __forceinline__ bool xcd_order(const FastTable &tab, int &wg) {
+  if (tab.NQB == 1) return true;
+  const int per = 8 * tab.NQB;
+  const int group = wg / per, within = wg - group * per;
+  const int qb = within >> 3, slot = group * 8 + (within & 7);
+  if (slot >= tab.n_slots) return false;
+  wg = slot * tab.NQB + qb;
+  return true;
+}
+
 __device__ __forceinline__ WgCoord decode_wg(const FastTable &tab, int wg) {
   WgCoord c;
   c.it = 0;
@@ -395,7 +409,9 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ uint32_t hist[64 * (kBins + 1)];
   __shared__ HistCtl ctl;
-  const WgCoord c = decode_wg(tab, blockIdx.x);
+  int wg_id = blockIdx.x;
+  if (!xcd_order(tab, wg_id)) return;
+  const WgCoord c = decode_wg(tab, wg_id);
   const FastItem I = tab.it[c.it];
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0u;
@@ -689,7 +705,9 @@ template <int DK>
 __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ EmitShared E;
-  const WgCoord c = decode_wg(tab, blockIdx.x);
+  int wg_id = blockIdx.x;
+  if (!xcd_order(tab, wg_id)) return;
+  const WgCoord c = decode_wg(tab, wg_id);
   const FastItem I = tab.it[c.it];
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int row_base = c.it * tab.rows_per_item;   // batch-local row index of (s = 0, h = 0)
@@ -947,19 +965,21 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       mask_off += (long long)tab.rows_per_item * f.W;
     }
     tab.sub_per_row = most_chunks * 2 * kWaves; tab.pad0 = 0;
+    tab.n_slots = part;
+    const int grid_wg = tab.NQB == 1 ? wg : ceil_div(part, 8) * 8 * tab.NQB;
     const int rows = nb * tab.rows_per_item;
     if (sh->head_dim == 128) {
-      hipLaunchKernelGGL(score_hist_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_hist_kernel<128>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(score_emit_kernel<128>, dim3(wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
     } else {
-      hipLaunchKernelGGL(score_hist_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_hist_kernel<64>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(score_emit_kernel<64>, dim3(wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_emit_kernel<64>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();
     hipLaunchKernelGGL((resolve_kernel<256, false>), dim3(ceil_div(rows, 4)), dim3(256), 0, st, tab, rows);
