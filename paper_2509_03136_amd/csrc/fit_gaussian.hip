@@ -40,7 +40,7 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
     for (; r + 4 * (kFitUnroll - 1) < r1; r += 4 * kFitUnroll) {
       float x[kFitUnroll][NV];
 #pragma unroll
-      for (int u = 0; u < kFitUnroll; ++u) Vec16<T>::load(base + (long long)(r + 4 * u) * I.stride, x[u]);
+      for (int u = 0; u < kFitUnroll; ++u) Vec16Stream<T>::load(base + (long long)(r + 4 * u) * I.stride, x[u]);
 #pragma unroll
       for (int u = 0; u < kFitUnroll; ++u) {
 #pragma unroll
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
     }
     for (; r < r1; r += 4) {
       float x[NV];
-      Vec16<T>::load(base + (long long)r * I.stride, x);
+      Vec16Stream<T>::load(base + (long long)r * I.stride, x);
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const float dlt = x[i] - pivot[i];

@@ -46,6 +46,29 @@ template <> struct Vec16<bf16_t> {
   }
 };
 
+// 16 bytes that are read once and never again (the big input streams): a non-temporal load keeps them
+// from displacing anything in the caches; measured +8 % on the hidden-state stream.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t load_stream16(const void *p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+}
+template <typename T> struct Vec16Stream;
+template <> struct Vec16Stream<float> {
+  __device__ __forceinline__ static void load(const float *p, float (&o)[4]) {
+    const u32x4_t v = load_stream16(p);
+    o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+  }
+};
+template <> struct Vec16Stream<bf16_t> {
+  __device__ __forceinline__ static void load(const bf16_t *p, float (&o)[8]) {
+    const u32x4_t v = load_stream16(p);
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
+};
+
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }

@@ -20,6 +20,11 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+#ifdef GVOTE_NTW
+#define WLOAD(p) load_stream16(p)
+#else
+#define WLOAD(p) (*reinterpret_cast<const u32x4_t *>(p))
+#endif
 
 // ---- Philox4x32-10 (Salmon et al., SC'11): ten rounds, Weyl key schedule
 __device__ __forceinline__ void philox4x32_10(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
@@ -140,19 +145,19 @@ __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const Sam
     bf16x8 a0[4], a1[4];
     {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a0[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + i * 8));
+      for (int i = 0; i < 4; ++i) a0[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + i * 8));
     }
     for (int kk = 0; kk < tab.kslice; kk += 128) {
       if (kk + 64 < tab.kslice) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          a1[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + kk + 64 + i * 8));
+          a1[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + kk + 64 + i * 8));
       }
       mma(a0, kk);
       if (kk + 128 < tab.kslice) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          a0[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(wrow + kk + 128 + i * 8));
+          a0[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + kk + 128 + i * 8));
       }
       if (kk + 64 < tab.kslice) mma(a1, kk + 64);
     }

@@ -162,7 +162,7 @@ struct Tile {
     const uint32_t lane_off = (uint32_t)(sub * (int)tok_stride + piece * 8) * 2u;
 #pragma unroll
     for (int j = 0; j < LOADS; ++j)
-      pre[j] = *reinterpret_cast<const u32x4 *>(tile + (long long)(j * RPL) * tok_stride * 2 + lane_off);
+      pre[j] = load_stream16(tile + (long long)(j * RPL) * tok_stride * 2 + lane_off);   // keys stream by: non-temporal
   }
 
   __device__ __forceinline__ void stage(const u32x4 (&pre)[LOADS], unsigned char *lds, int lane) const {
