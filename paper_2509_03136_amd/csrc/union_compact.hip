@@ -146,10 +146,11 @@ __global__ __launch_bounds__(256) void gather_kernel(const UnionTable tab) {
       if (dst >= tab.capacity) break;
       const int t = list[i];
       const long long src = (long long)t * I.tok_stride + piece * EPP;
-      const uint4 kx = *reinterpret_cast<const uint4 *>(kb + src);
-      const uint4 vx = *reinterpret_cast<const uint4 *>(vb + src);
-      *reinterpret_cast<uint4 *>(ko + dst * dk + piece * EPP) = kx;
-      *reinterpret_cast<uint4 *>(vo + dst * dk + piece * EPP) = vx;
+      // kept rows are read once and written once: non-temporal both ways, the caches stay with W_q
+      const u32x4_t kx = load_stream16(kb + src);
+      const u32x4_t vx = load_stream16(vb + src);
+      __builtin_nontemporal_store(kx, reinterpret_cast<u32x4_t *>(ko + dst * dk + piece * EPP));
+      __builtin_nontemporal_store(vx, reinterpret_cast<u32x4_t *>(vo + dst * dk + piece * EPP));
       if (piece == 0 && tab.idx_out) tab.idx_out[dst] = t;
     }
   }
