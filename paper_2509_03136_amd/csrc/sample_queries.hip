@@ -20,11 +20,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-#ifdef GVOTE_NTW
-#define WLOAD(p) load_stream16(p)
-#else
-#define WLOAD(p) (*reinterpret_cast<const u32x4_t *>(p))
-#endif
 
 // ---- Philox4x32-10 (Salmon et al., SC'11): ten rounds, Weyl key schedule
 __device__ __forceinline__ void philox4x32_10(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
@@ -111,27 +106,41 @@ __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const Sam
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hf = lane >> 5;
-  // rows beyond n_out re-read the last row (their products are never stored): no guard on the loads
-  const int o = min(blockIdx.x * (kProjWaves * 32) + wave * 32 + col, tab.n_out - 1);
-  const bf16_t *wrow = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)o * tab.d + k0 + hf * 32;
   floatx16 acc[NSB];
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[sb][r] = 0.f;
 
-  // one k-step = 64 channels: lane (row, hf) owns channels hf*32 .. hf*32+31 of its row, consumed
-  // 8 at a time by four MFMAs; the B operand uses the very same channel assignment.  Two k-steps of
-  // W_q are in flight ahead of the MFMAs.
-  auto load_a = [&](bf16x8(&a)[4], int kk) __attribute__((always_inline)) {
+  // One k-step = 64 channels = 128 bytes of each of the wave's 32 W_q rows.  The rows are fetched with
+  // fully coalesced non-temporal loads (8 lanes x 16 B cover a row's 128 bytes, a wave-wide load takes 8
+  // rows), dropped into a wave-private XOR-swizzled LDS tile and read back in MFMA operand order: lane
+  // (row, hf) takes channels hf*32 + i*8 .. +7 for MFMA i, the B operand uses the same assignment.  The
+  // next k-step's loads are in flight while the current one is multiplied.  Rows beyond n_out re-read the
+  // last row (their products are never stored); a shorter last k-slice takes the guarded path below.
+  unsigned char *wtile = smem + (size_t)32 * NSB * ldb * sizeof(bf16_t) + wave * 4096;
+  const int ob = blockIdx.x * (kProjWaves * 32) + wave * 32;
+  const int lrow = lane >> 3, lpiece = lane & 7;
+  const bf16_t *wbase = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + k0 + lpiece * 8;
+  auto fetch_w = [&](u32x4_t(&w)[4], int kk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (klen == tab.kslice || kk + hf * 32 + i * 8 < klen) raw = *reinterpret_cast<const uint4 *>(wrow + kk + i * 8);
-      a[i] = __builtin_bit_cast(bf16x8, raw);
+    for (int j = 0; j < 4; ++j) {
+      const int o = min(ob + 8 * j + lrow, tab.n_out - 1);
+      w[j] = load_stream16(wbase + (size_t)o * tab.d + kk);
     }
   };
-  auto mma = [&](const bf16x8(&a)[4], int kk) __attribute__((always_inline)) {
+  auto stage_w = [&](const u32x4_t(&w)[4]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = 8 * j + lrow;
+      *reinterpret_cast<u32x4_t *>(wtile + row * 128 + ((lpiece ^ (row & 7)) << 4)) = w[j];
+    }
+  };
+  auto mma = [&](int kk) __attribute__((always_inline)) {
+    bf16x8 a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      a[i] = *reinterpret_cast<const bf16x8 *>(wtile + col * 128 + (((hf * 4 + i) ^ (col & 7)) << 4));
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
 #pragma unroll
@@ -142,36 +151,48 @@ __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const Sam
     }
   };
   if (klen == tab.kslice) {          // full slice: straight-line loads
-    bf16x8 a0[4], a1[4];
-    {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a0[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + i * 8));
-    }
+    u32x4_t w0[4], w1[4];            // two k-steps in flight
+    const int klast = tab.kslice - 64;
+    fetch_w(w0, 0);
+    fetch_w(w1, min(64, klast));
     for (int kk = 0; kk < tab.kslice; kk += 128) {
+      stage_w(w0);
+      fetch_w(w0, min(kk + 128, klast));             // (past the end a step is fetched again: no conditional load)
+      __builtin_amdgcn_wave_barrier();
+      mma(kk);
+      __builtin_amdgcn_wave_barrier();
       if (kk + 64 < tab.kslice) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          a1[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + kk + 64 + i * 8));
+        stage_w(w1);
+        fetch_w(w1, min(kk + 192, klast));
+        __builtin_amdgcn_wave_barrier();
+        mma(kk + 64);
+        __builtin_amdgcn_wave_barrier();
       }
-      mma(a0, kk);
-      if (kk + 128 < tab.kslice) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          a0[i] = __builtin_bit_cast(bf16x8, WLOAD(wrow + kk + 128 + i * 8));
-      }
-      if (kk + 64 < tab.kslice) mma(a1, kk + 64);
     }
-  } else {                           // the last, shorter slice: guarded
+  } else {                           // the last, shorter slice: guarded element-wise loads
+    const int o = min(ob + col, tab.n_out - 1);
+    const bf16_t *wrow = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)o * tab.d + k0 + hf * 32;
     for (int kk = 0; kk < tab.kslice; kk += 64) {
       bf16x8 a[4];
-      load_a(a, kk);
-      mma(a, kk);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (kk + hf * 32 + i * 8 < klen) raw = *reinterpret_cast<const uint4 *>(wrow + kk + i * 8);
+        a[i] = __builtin_bit_cast(bf16x8, raw);
+      }
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint4 raw = *reinterpret_cast<const uint4 *>(Bs + (sb * 32 + col) * ldb + kk + hf * 32 + i * 8);
+          acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], __builtin_bit_cast(bf16x8, raw), acc[sb], 0, 0, 0);
+        }
+      }
     }
   }
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   // Rows are outputs o, columns are samples.
   float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
-  const int ob = blockIdx.x * (kProjWaves * 32) + wave * 32;
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
 #pragma unroll
@@ -324,7 +345,7 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
     if (mfma) {
       const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, nb);
       const int nsb = plan.SP / 32;
-      const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t);
+      const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
       if (nsb == 3)
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
