@@ -37,6 +37,22 @@ def algorithmic_bytes(wl, lengths, rho):
     return dict(fit=fit, sample=proj, select=score, compact=compact, total=fit + proj + score + compact)
 
 
+def profiled_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "cfg3_hbm_traffic_pmc.txt")
+    if workload != "cfg3_llama8b_stack_32k" or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith(kernel):
+            cols = line[38:].split()
+            try:
+                return (float(cols[2]) + float(cols[3])) * 1e6
+            except (IndexError, ValueError):
+                return None
+    return None
+
+
 def cpu_baseline(wl, items, n_sample):
     import numpy as np
     import parity_util as U
@@ -122,7 +138,10 @@ def main():
     dom = max(stage_ms, key=stage_ms.get)
     dom_kernel = {"fit": "moments_partial_kernel", "sample": "project_mfma_kernel",
                   "select": "score_hist_kernel", "compact": "gather_kernel"}[dom]
-    traffic = None if args.traffic_kib is None else (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
+    if args.traffic_kib is not None:
+        traffic = (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
+    else:
+        traffic = profiled_traffic(wl.name, dom_kernel)
     ach = ab[dom] / (stage_ms[dom] * 1e-3) / 1e9
     out = {
         "metric": "KV tokens selected+compacted/sec (all layers, 32k ctx); achieved HBM GB/s vs peak",
