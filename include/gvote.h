@@ -170,6 +170,14 @@ GVOTE_API gvote_status gvote_union_compact(const gvote_shape *shape, const gvote
                                  int64_t capacity_tokens, int32_t *overflow_flag,
                                  void *ws, size_t ws_bytes, void *stream);
 
+/* Alg. 1 "B_step <- |C_0|": sizes of row sets.  counts[i, c, r] (device int32, [n_items, repeat, S * n_q_heads])
+ * = number of keys selected in row r of item i's row masks, written `repeat` times over.  With the masks
+ * of the REAL current query (S = 1, GVOTE_SELECT_TOPP) and repeat = number of synthetic samples, the
+ * output is exactly the k_per_row that GVOTE_SELECT_TOPK expects for the synthetic rows (row s * n_q_heads
+ * + h gets the budget of head h): Alg. 1's row-wise TopK with the real query's budget.  repeat >= 1. */
+GVOTE_API gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
+                                        const uint32_t *rowmask, int32_t repeat, int32_t *counts, void *stream);
+
 /* Test aid: out[e] (device uint32, e < n) = Philox4x32-10 draw e of stream (seed, stream_id),
  * the integer stream gvote_sample_queries consumes. */
 GVOTE_API gvote_status gvote_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, void *stream);

@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
     L.gvote_score_select.argtypes = [sp, ip, i32, i32, vp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
     L.gvote_union_compact.restype = C.c_int
     L.gvote_union_compact.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.gvote_count_rows.restype = C.c_int
+    L.gvote_count_rows.argtypes = [sp, ip, i32, i32, vp, i32, vp, vp]
     L.gvote_philox_u32.restype = C.c_int
     L.gvote_philox_u32.argtypes = [u64, u64, i64, vp, vp]
     _lib = L
@@ -167,6 +169,11 @@ def union_compact(b: Batch, S: int, rowmask: torch.Tensor, union_mask: torch.Ten
                                      _ptr(budget), _ptr(offsets), _ptr(k_out), _ptr(v_out), _ptr(idx_out),
                                      int(capacity_tokens), _ptr(overflow_flag), _ptr(ws),
                                      ws.numel() * ws.element_size(), _stream(stream)), "gvote_union_compact")
+
+
+def count_rows(b: Batch, S: int, rowmask: torch.Tensor, repeat: int, counts: torch.Tensor, stream=None) -> None:
+    _check(lib().gvote_count_rows(C.byref(b.shape), b.items, b.n_items, S, _ptr(rowmask), int(repeat), _ptr(counts),
+                                  _stream(stream)), "gvote_count_rows")
 
 
 def philox_u32(seed: int, stream_id: int, n: int, out: torch.Tensor, stream=None) -> None:

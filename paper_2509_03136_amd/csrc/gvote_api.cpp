@@ -150,6 +150,16 @@ gvote_status gvote_union_compact(const gvote_shape *shape, const gvote_item *ite
                               overflow_flag, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
+gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
+                              const uint32_t *rowmask, int32_t repeat, int32_t *counts, void *stream) {
+  gvote_status st = check_shape(shape);
+  if (st != GVOTE_OK) return st;
+  if ((st = check_items(shape, items, n_items, 0)) != GVOTE_OK) return st;
+  if (!rowmask || !counts || S < 1 || repeat < 1) return GVOTE_ERR_INVALID_ARG;
+  if (S > 128) return GVOTE_ERR_CAPACITY;
+  return launch_count_rows(shape, items, n_items, S, rowmask, repeat, counts, reinterpret_cast<hipStream_t>(stream));
+}
+
 gvote_status gvote_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, void *stream) {
   if (n < 0 || (n > 0 && !out)) return GVOTE_ERR_INVALID_ARG;
   return launch_philox_u32(seed, stream_id, n, out, reinterpret_cast<hipStream_t>(stream));

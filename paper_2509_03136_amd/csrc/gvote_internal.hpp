@@ -303,6 +303,9 @@ gvote_status launch_union_compact(const gvote_shape *sh, const gvote_item *items
                                   void *k_out, void *v_out, int *idx_out, long long capacity, int *overflow_flag,
                                   void *ws, hipStream_t st);
 
+gvote_status launch_count_rows(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
+                               const uint32_t *rowmask, int repeat, int *counts, hipStream_t st);
+
 #define GVOTE_CHECK_LAUNCH()                                  \
   do {                                                        \
     if (hipGetLastError() != hipSuccess) return GVOTE_ERR_HIP; \

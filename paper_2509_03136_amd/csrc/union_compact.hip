@@ -156,7 +156,48 @@ __global__ __launch_bounds__(256) void gather_kernel(const UnionTable tab) {
   }
 }
 
+// one wave per row: popcount of the row's words; grid (ceil(rows / 4)), item geometry by value
+struct CountTable {
+  int n_items, rows_per_item, repeat, item0;
+  const uint32_t *rowmask;
+  int *counts;
+  long long mask_off[kMaxItems];
+  int W[kMaxItems];
+};
+__global__ __launch_bounds__(256) void count_rows_kernel(const CountTable tab) {
+  const int lane = threadIdx.x & 63;
+  const int grow = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grow >= tab.n_items * tab.rows_per_item) return;
+  const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
+  const uint32_t *row = tab.rowmask + tab.mask_off[it] + (long long)r * tab.W[it];
+  int n = 0;
+  for (int w = lane; w < tab.W[it]; w += 64) n += __popc(row[w]);
+  for (int off = 32; off > 0; off >>= 1) n += __shfl_xor(n, off, 64);
+  if (lane == 0)
+    for (int c = 0; c < tab.repeat; ++c)
+      tab.counts[((size_t)(tab.item0 + it) * tab.repeat + c) * tab.rows_per_item + r] = n;
+}
+
 }  // namespace
+
+gvote_status launch_count_rows(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
+                               const uint32_t *rowmask, int repeat, int *counts, hipStream_t st) {
+  long long off = 0;
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    CountTable tab;
+    tab.n_items = nb; tab.rows_per_item = S * sh->n_q_heads; tab.repeat = repeat; tab.item0 = b0;
+    tab.rowmask = rowmask; tab.counts = counts;
+    for (int i = 0; i < nb; ++i) {
+      tab.W[i] = (items[b0 + i].L + 31) / 32;
+      tab.mask_off[i] = off;
+      off += (long long)tab.rows_per_item * tab.W[i];
+    }
+    hipLaunchKernelGGL(count_rows_kernel, dim3(ceil_div(nb * tab.rows_per_item, 4)), dim3(256), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+  }
+  return GVOTE_OK;
+}
 
 UnionPlan plan_union(const gvote_shape *sh, const gvote_item *items, int n_items) {
   UnionPlan p;

@@ -26,7 +26,8 @@ def declared_symbols():
 def test_header_symbols_are_exported(g):
     names = declared_symbols()
     assert {"gvote_fit_gaussian", "gvote_sample_queries", "gvote_score_select", "gvote_union_compact",
-            "gvote_workspace_bytes", "gvote_status_string", "gvote_abi_version", "gvote_philox_u32"} <= set(names)
+            "gvote_workspace_bytes", "gvote_status_string", "gvote_abi_version", "gvote_philox_u32",
+            "gvote_count_rows"} <= set(names)
     lib = C.CDLL(g.lib_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -113,6 +114,8 @@ def test_bad_arguments_are_rejected_before_any_launch(g):
                None) == INVALID
     assert uni(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, 0x400, 0x500, 0x600, None, 10, 0x700, ws, 8,
                None) == WS
+    assert L.gvote_count_rows(C.byref(sh), it, 1, 1, None, 8, 0x100, None) == INVALID
+    assert L.gvote_count_rows(C.byref(sh), it, 1, 1, 0x100, 0, 0x200, None) == INVALID
     assert L.gvote_philox_u32(1, 2, -1, None, None) == INVALID
     assert L.gvote_philox_u32(1, 2, 0, None, None) == 0
 

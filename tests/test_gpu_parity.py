@@ -399,3 +399,95 @@ def test_end_to_end_path(g, name):
         assert np.all(np.abs(pipe.row_max[i].cpu().numpy() - m) <= tol * (1 + np.abs(m)))
         say(f"  item {i}: L={L} budget gpu {budget[i].tolist()} oracle {r['budget'].tolist()}")
     say("  boundary keys", boundary)
+
+
+def test_repeat_runs_are_bit_identical(g):
+    """Integer histograms, ordered compaction and fixed-order reductions: the same call twice gives the
+    same bits (masks, budgets, packed cache, moments, queries)."""
+    wl = small_workloads()["cfg3_small"]
+    items = W.make_items(wl, "cpu")
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    outs = []
+    for _ in range(2):
+        pipe = g.Pipeline(b, wl.S, wl.p, ddof=wl.ddof)
+        pipe.run()
+        torch.cuda.synchronize()
+        n = int(pipe.offsets[-1].item())
+        outs.append((pipe.mu.clone(), pipe.var.clone(), pipe.q.clone(), pipe.rowmask.clone(), pipe.union_mask.clone(),
+                     pipe.budget.clone(), pipe.k_out[:n].clone(), pipe.idx_out[:n].clone()))
+    for a, c in zip(*outs):
+        assert torch.equal(a, c)
+
+
+def test_short_contexts_take_the_general_path(g):
+    """bf16 items with fewer than 32 keys (the matrix-core path loads whole 32-key tiles)."""
+    wl = W.scaled(W.config(2), lengths=(31, 17, 40), S=4)
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it) for it in items]
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, wl.p)
+    pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+    pipe.select()
+    torch.cuda.synchronize()
+    off = 0
+    for i, (it, r) in enumerate(zip(items, refs)):
+        L = it["L"]
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
+        off += pipe.mask_words[i]
+        U.check_rowmask_sandwich(gm, r["logits"], U.p32(wl.p), U.STAGE_TOL[wl.dtype])
+
+
+def test_algorithm1_mode_real_query_budget_then_topk(g):
+    """The paper's Algorithm 1 as printed: the REAL current query's top-p set sizes B_step per head, then
+    every synthetic row keeps its B_step largest logits (row-wise TopK), then the union.  Composed from
+    gvote_score_select (TOPP, S = 1) -> gvote_count_rows -> gvote_score_select (TOPK) -> gvote_union_compact."""
+    wl = W.scaled(W.config(2), lengths=(1800, 700), n_planted=(30, 10), S=8)
+    items = W.make_items(wl, "cpu")
+    dev_items = U.to_device(items, DEV)
+    b = U.batch_from(g, wl, dev_items)
+    n, S, hq = len(items), wl.S, wl.n_q_heads
+    refs = [U.oracle_item(wl, it) for it in items]
+    p = U.p32(wl.p)
+    # the real current query of each item: the last token's hidden state through W_q, rotated at L - 1
+    q0 = []
+    for it in items:
+        L = it["L"]
+        c, s_ = O.rope_cos_sin(float(np.float32(wl.theta)), wl.d_k, L - 1, 1)
+        q0.append(O.project_rope(U.f32np(it["hidden"][L - 1:L]), U.f32np(it["w_q"]), None, c, s_, hq, wl.d_k, wl.dtype))
+    q0_dev = torch.tensor(np.stack(q0)).to(torch.bfloat16).to(DEV)                 # [n, 1, H_q, d_k]
+    words = [b.words(i) for i in range(n)]
+    mask0 = torch.empty(sum(hq * w for w in words), device=DEV, dtype=torch.int32)
+    ws = torch.empty(g.workspace_bytes(b, S), device=DEV, dtype=torch.uint8)
+    g.score_select(b, 1, q0_dev, p, mask0, ws=ws)
+    counts = torch.empty(n, S, hq, device=DEV, dtype=torch.int32)
+    g.count_rows(b, 1, mask0, S, counts)
+    pipe = g.Pipeline(b, S, p)
+    pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+    g.score_select(b, S, pipe.q, p, pipe.rowmask, mode=g.SELECT_TOPK, k_per_row=counts, ws=pipe.ws)
+    pipe.compact()
+    torch.cuda.synchronize()
+    counts_h = counts.cpu().numpy()
+    off0 = off = uoff = 0
+    swaps = 0
+    for i, (it, r) in enumerate(zip(items, refs)):
+        L = it["L"]
+        lg0 = O.scores(q0[i], U.f32np(it["k"]))[0]                      # [H_q, L]
+        m0 = U.unpack_rows(mask0[off0:off0 + hq * words[i]], hq, L)
+        off0 += hq * words[i]
+        for h in range(hq):
+            must, may = U.band_sets(lg0[h], p, U.STAGE_TOL["bf16"])
+            assert not (must & ~m0[h]).any() and not (m0[h] & ~may).any()
+            assert np.all(counts_h[i, :, h] == m0[h].sum())
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(S, hq, L)
+        off += pipe.mask_words[i]
+        for s in range(S):
+            for h in range(hq):
+                k = int(counts_h[i, s, h])
+                assert gm[s, h].sum() == k
+                swaps += int((gm[s, h] ^ O.top_k_select(r["logits"][s, h], k)).sum())
+        um = U.unpack_rows(pipe.union_mask[uoff:uoff + pipe.union_words[i]], wl.n_kv_heads, L)
+        uoff += pipe.union_words[i]
+        gu, gb = O.union_vote(gm, wl.n_kv_heads)
+        assert np.array_equal(um, gu) and np.array_equal(pipe.budget[i].cpu().numpy(), gb)
+        say(f"  item {i}: B_step per head {counts_h[i, 0].tolist()[:8]}..., union budget {gb.tolist()}")
+    assert swaps <= 8          # only fp32-vs-fp64 near-ties may swap

@@ -356,3 +356,33 @@ def test_path_invariants_on_tiny_workload():
     # S = 1 with one head per group reduces to the single query's threshold set
     lg = one["logits"]
     assert np.array_equal(one["rowmask"][0, 0], O.top_p_select(lg[0, 0], 0.5))
+
+
+# ---------------------------------------------------------------- test infrastructure itself
+def test_band_sets_bracket_the_oracle_selection():
+    import sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    import parity_util as U
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        l = rng.normal(scale=2.0, size=200)
+        p = float(rng.uniform(0.5, 0.99))
+        sel = O.top_p_select(l, p)
+        must, may = U.band_sets(l, p, 1e-3)
+        assert np.all(sel[must]) and np.all(may[sel])
+        must0, may0 = U.band_sets(l, p, 0.0)
+        # with no tolerance only the key that crosses p is free
+        assert (may0 & ~must0).sum() <= 1 and np.all(sel[must0]) and np.all(may0[sel])
+
+
+def test_workload_generator_is_seeded_and_shaped():
+    from synth import workloads as W
+    wl = W.scaled(W.config(5), lengths=(200, 90))
+    a, b = W.make_items(wl, "cpu"), W.make_items(wl, "cpu")
+    for x, y in zip(a, b):
+        for k in ("hidden", "w_q", "k", "v"):
+            assert x[k].dtype == wl.torch_dtype and bool((x[k] == y[k]).all())
+    assert a[0]["hidden"].shape == (200, wl.d) and a[1]["k"].shape == (90, wl.n_kv_heads, wl.d_k)
+    assert a[0]["w_q"].data_ptr() == a[1]["w_q"].data_ptr()          # one layer, many requests
+    assert [W.config(i).n_items for i in range(1, 6)] == [1, 1, 32, 28, 16]
+    assert min(W.config(5).lengths) >= 1024 and max(W.config(5).lengths) <= 16384
