@@ -239,6 +239,7 @@ struct FastTable {
   int n_items, S, Hq, Hkv, G, NQ, NQB, chunk_keys;
   int item0, rows_per_item;
   int n_slots;              // (item, KV head, chunk) slots of the batch
+  int emit_split, pad4;     // pass 2 cuts every chunk into this many pieces of at most 8192 keys (its LDS mask buffer)
   int sub_per_row, pad0;    // candidate sub-lists per row = 16 * (most key chunks of an item in the batch)
   float scale, c1, c2, p;   // c1 = bins per raw-dot unit, c2 = log2(e) / sqrt(d_k)
   const void *q;

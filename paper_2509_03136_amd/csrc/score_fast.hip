@@ -56,11 +56,11 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u) {
 // Fixed-point histogram bins (integer LDS atomics run ~30x faster than float ones on this chip).
 // Bins live on an absolute grid of the raw dot product d: a = floor(d * c1), 16 bins per unit of
 // logit.  A key adds exp((l - E_a)) * 2^kFixBits to its bin, E_a the bin's UPPER edge, so every term
-// lies in (0.94, 1] * 2^18 whatever the row maximum is, and a chunk of <= 8192 keys cannot overflow
+// lies in (0.94, 1] * 2^17 whatever the row maximum is, and a chunk of <= 16384 keys cannot overflow
 // 32 bits.  Bin j of a row is absolute bin top - j (top = bin of the row maximum); everything deeper
 // than kBins - 1 bins is clamped into the last bin, measured against that bin's edge (such keys weigh
 // < 1.2e-7 of the maximum each; below 2^-19 of the edge they round to nothing).
-constexpr int kFixBits = 18;
+constexpr int kFixBits = 17;
 constexpr float kLog2ePerBin = 1.44269504088896340736f / (float)kBinsPerUnit;   // log2 weight per bin
 
 // integer add to a 32-bit word of LDS given its byte address inside the workgroup's LDS
@@ -341,7 +341,7 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
 #if (GVOTE_ABL & 1)
     return;
 #endif
-    // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 18),
+    // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 17),
     // truncated (a uniform -2e-6 relative bias that cancels in every ratio of sums); LDS byte address
     // hrow + 4 (top - a), formed in fp32 (exact: all quantities are small integers).
     if (skip == 0) {
@@ -536,7 +536,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
 // Pass 1 left the maximum of every (tile, row).  A tile in which no row reaches its cut bin selects
 // nothing, so its keys are not even fetched: the second K read shrinks to the tiles that matter
 // (attention mass is concentrated, most tiles hold no selected key for any of the 64 rows).
-constexpr int kMaxChunkWords = 8 * kRoundKeys / 32;     // mask words per row of the largest chunk (256)
+constexpr int kMaxChunkWords = 8 * kRoundKeys / 32;     // mask words per row of the largest pass-2 piece (256)
 struct EmitShared {
   uint32_t mwords[64][kMaxChunkWords + 1];
   int astar[64];
@@ -705,10 +705,17 @@ template <int DK>
 __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ EmitShared E;
-  int wg_id = blockIdx.x;
+  int wg_id = blockIdx.x / tab.emit_split;
+  const int piece = blockIdx.x - wg_id * tab.emit_split;
   if (!xcd_order(tab, wg_id)) return;
-  const WgCoord c = decode_wg(tab, wg_id);
+  WgCoord c = decode_wg(tab, wg_id);
   const FastItem I = tab.it[c.it];
+  {   // this workgroup's piece of the chunk (possibly empty at the end of an item: its counts are still written)
+    const int piece_keys = tab.chunk_keys / tab.emit_split;
+    c.t_begin = min(c.t_begin + piece * piece_keys, c.t_end);
+    c.t_end = min(c.t_end, c.t_begin + piece_keys);
+    c.chunk = c.chunk * tab.emit_split + piece;     // numbers the candidate sub-lists
+  }
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int row_base = c.it * tab.rows_per_item;   // batch-local row index of (s = 0, h = 0)
   if (tid < 64) {
@@ -776,7 +783,7 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   double above = info->above * unit;
 
   // gather the sub-lists (order is irrelevant: keys are unique)
-  const int n_sub = I.n_chunks * 2 * kWaves;
+  const int n_sub = I.n_chunks * tab.emit_split * 2 * kWaves;
   int cnt = 0;
   for (int s0 = 0; s0 < n_sub; s0 += 64) {
     const int sub = s0 + lane;
@@ -866,16 +873,20 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   }
 }
 
+constexpr int kMaxChunkKeys = 16 * kRoundKeys;     // pass 1: the 32-bit fixed-point bins hold 16384 keys
+constexpr int kMaxEmitKeys = 8 * kRoundKeys;       // pass 2: its LDS mask buffer holds 8192 keys per row
 int pick_chunk_keys(const gvote_shape *sh, const gvote_item *items, int n_items) {
-  // about four workgroups per CU over the batch; a chunk is a whole number of emit rounds
+  // about two pass-1 workgroups per CU over the batch (per-chunk set-up and the flush of the histograms
+  // are not free); a chunk is a whole number of 1024-key rounds
   long long keys = 0;
   for (int i = 0; i < n_items; ++i) keys += (long long)items[i].L * sh->n_kv_heads;
-  long long ck = (keys + 1023) / 1024;
+  long long ck = (keys + 511) / 512;
   ck = (ck + kRoundKeys - 1) / kRoundKeys * kRoundKeys;
   if (ck < kRoundKeys) ck = kRoundKeys;
-  if (ck > 8 * kRoundKeys) ck = 8 * kRoundKeys;
+  if (ck > kMaxChunkKeys) ck = kMaxChunkKeys;
   return (int)ck;
 }
+int emit_split_of(int chunk_keys) { return chunk_keys > kMaxEmitKeys ? 2 : 1; }
 
 }  // namespace
 
@@ -894,7 +905,7 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
     const int ck = pick_chunk_keys(sh, items + b0, nb);
     size_t slots = 0, tiles = 0;
     for (int i = 0; i < nb; ++i) {
-      const size_t sub = (size_t)ceil_div(items[b0 + i].L, ck) * 2 * kWaves;
+      const size_t sub = (size_t)ceil_div(items[b0 + i].L, ck) * emit_split_of(ck) * 2 * kWaves;
       if (sub > max_sub) max_sub = sub;
       slots += (size_t)sh->n_kv_heads * ceil_div(items[b0 + i].L, ck);
       tiles += (size_t)sh->n_kv_heads * ((items[b0 + i].L + 31) / 32);
@@ -964,7 +975,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       part += sh->n_kv_heads * f.n_chunks;
       mask_off += (long long)tab.rows_per_item * f.W;
     }
-    tab.sub_per_row = most_chunks * 2 * kWaves; tab.pad0 = 0;
+    tab.emit_split = emit_split_of(tab.chunk_keys); tab.pad4 = 0;
+    tab.sub_per_row = most_chunks * tab.emit_split * 2 * kWaves; tab.pad0 = 0;
     tab.n_slots = part;
     const int grid_wg = tab.NQB == 1 ? wg : ceil_div(part, 8) * 8 * tab.NQB;
     const int rows = nb * tab.rows_per_item;
@@ -973,13 +985,13 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
     } else {
       hipLaunchKernelGGL(score_hist_kernel<64>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
-      hipLaunchKernelGGL(score_emit_kernel<64>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      hipLaunchKernelGGL(score_emit_kernel<64>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();
     hipLaunchKernelGGL((resolve_kernel<256, false>), dim3(ceil_div(rows, 4)), dim3(256), 0, st, tab, rows);
