@@ -491,3 +491,31 @@ def test_algorithm1_mode_real_query_budget_then_topk(g):
         assert np.array_equal(um, gu) and np.array_equal(pipe.budget[i].cpu().numpy(), gb)
         say(f"  item {i}: B_step per head {counts_h[i, 0].tolist()[:8]}..., union budget {gb.tolist()}")
     assert swaps <= 8          # only fp32-vs-fp64 near-ties may swap
+
+
+def test_more_items_than_one_launch_table_bf16(g):
+    """40 requests in one call: every stage splits the batch into launch tables of 32 items."""
+    lengths = tuple(64 + 37 * (i % 9) + i for i in range(40))
+    wl = W.scaled(W.config(5), lengths=lengths, n_planted=tuple(1 + i % 4 for i in range(40)), S=4)
+    items = W.make_items(wl, "cpu")
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, wl.p, ddof=wl.ddof)
+    pipe.run()
+    torch.cuda.synchronize()
+    budget = pipe.budget.cpu().numpy()
+    offsets = pipe.offsets.cpu().numpy()
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(budget.reshape(-1))]))
+    moff = np.concatenate([[0], np.cumsum(pipe.mask_words)])
+    uoff = np.concatenate([[0], np.cumsum(pipe.union_words)])
+    for i in (0, 31, 32, 39):
+        it, L = items[i], lengths[i]
+        r = U.oracle_item(wl, it)
+        gm = U.unpack_rows(pipe.rowmask[moff[i]:moff[i + 1]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
+        U.check_rowmask_sandwich(gm, r["logits"], U.p32(wl.p), U.TOL[wl.dtype])
+        um = U.unpack_rows(pipe.union_mask[uoff[i]:uoff[i + 1]], wl.n_kv_heads, L)
+        gu, gb = O.union_vote(gm, wl.n_kv_heads)
+        assert np.array_equal(um, gu) and np.array_equal(budget[i], gb)
+        ko, vo, idx, _ = O.compact(U.f32np(it["k"]), U.f32np(it["v"]), um)
+        lo, hi = offsets[i * wl.n_kv_heads], offsets[(i + 1) * wl.n_kv_heads]
+        assert np.array_equal(U.f32np(pipe.k_out[lo:hi]), ko) and np.array_equal(pipe.idx_out[lo:hi].cpu().numpy(), idx)
+        assert np.all(np.abs(pipe.mu[i].cpu().numpy() - r["mu"]) <= 1e-5 * np.maximum(np.abs(r["mu"]), np.sqrt(r["var"])) + 1e-7)
