@@ -14,10 +14,11 @@
 //                above a* are selected outright (bit masks, transposed in LDS so every row writes
 //                whole 128-byte runs); keys inside bin a* are appended (raw dot, position) to the
 //                row's candidate list.
-//   resolve      per row: exact selection among the candidates - radix search over the 64-bit
-//                key (ordered dot, ~position), so ties go to the lower position - and OR of the
-//                chosen bits into the mask.
-// Rows whose cut falls into the collecting bin, or whose candidate lists overflow, are flagged
+//   resolve      per row (one wave): exact selection among the candidates in the order (raw dot
+//                descending, position ascending), so ties go to the lower position - a pairwise
+//                "weight ahead of me" test for up to 64 candidates, a radix search beyond - and OR
+//                of the chosen bits into the mask.
+// Rows whose cut falls below the histogram window, or whose candidate lists overflow, are queued
 // and redone by the exact general selector (select_row_kernel).
 //
 // A workgroup is 8 waves; a wave owns 32-key tiles.  K rows of a tile are fetched with fully
@@ -27,9 +28,6 @@
 // x 32 query rows (kept in registers for the whole kernel), C[key][query row]: a lane owns ONE
 // query row and 16 keys, so row statistics need no cross-lane traffic inside the loop.
 #include "gvote_internal.hpp"
-#ifndef GVOTE_ABL
-#define GVOTE_ABL 0   // kernel-timing experiments only: 1 = no binning, 3 = also no maxima/events, 7 = also no MFMA
-#endif
 
 namespace gvote {
 
@@ -300,18 +298,8 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
       T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
     }
     __builtin_amdgcn_wave_barrier();
-#if (GVOTE_ABL & 4)
-    { const uint32_t gx = *reinterpret_cast<const uint32_t *>(ldstile + lane * 16);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { acc[0][r] = __uint_as_float(gx & 0x3FFFFFFFu); acc[1][r] = acc[0][r]; } }
-#else
     T.template compute<TWO>(acc, ldstile, lane);
-#endif
     __builtin_amdgcn_wave_barrier();
-#if (GVOTE_ABL & 2)
-    mxrun[0] = fmaxf(mxrun[0], acc[0][0] + acc[1][15]);
-    return;
-#endif
     // (keys ahead of a pulled-back tile are keys of the same row: they may enter the maxima, never the bins)
     float mx0 = acc[0][0], mx1 = acc[1][0];
 #pragma unroll
@@ -338,9 +326,6 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
       event = __builtin_amdgcn_readfirstlane(pend_seen) != 0;
     }
     if (event) sync_event();
-#if (GVOTE_ABL & 1)
-    return;
-#endif
     // Bin of a key: a = max(floor(d c1), top - 255); fixed-point term 2^(d c2 - (a + 1) log2e/16 + 17),
     // truncated (a uniform -2e-6 relative bias that cancels in every ratio of sums); LDS byte address
     // hrow + 4 (top - a), formed in fp32 (exact: all quantities are small integers).
@@ -585,9 +570,6 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) cdst[nb] = tab.cands + ((size_t)grow[nb] * tab.sub_per_row + sub) * kSubCap;
 
-#if (GVOTE_ABL & 32)
-  need = 0u;
-#endif
   uint32_t todo = need;        // tiles not yet fetched
   auto next_k = [&]() __attribute__((always_inline)) -> int {
     if (todo == 0u) return -1;
@@ -613,9 +595,6 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
     __builtin_amdgcn_wave_barrier();
     // floor(d * c1) >= astar  <=>  d * c1 >= astar (astar is an integer): two compares, no floor
     uint32_t ge[2] = {0u, 0u}, gt[2] = {0u, 0u};
-#if (GVOTE_ABL & 16)
-    gt[0] = (acc[0][0] + acc[1][3]) == 12345.f ? 1u : 0u;
-#else
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       if (nb == 0 || TWO) {
@@ -628,13 +607,12 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
         }
       }
     }
-#endif
     if (skip) {                          // wave-uniform: a pulled-back last tile
       const uint32_t mine = 0xFFFFFFFFu << skip;
       ge[0] &= mine; ge[1] &= mine; gt[0] &= mine; gt[1] &= mine;
     }
     const uint32_t cm[2] = {ge[0] & ~gt[0], ge[1] & ~gt[1]};
-    if (!(GVOTE_ABL & 8) && __any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
+    if (__any((cm[0] | cm[1]) != 0u)) {   // keys inside a cut bin go to this lane's own sub-lists: no atomics
       // accumulator registers 4g .. 4g+3 hold four neighbouring keys: one wave-uniform test per group
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
