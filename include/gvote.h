@@ -143,6 +143,7 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * device int32, clamped to [1, L]; pass NULL for TOPP).  Ties are broken towards the lower position.
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
  * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
+ * ws is required (gvote_workspace_bytes): statistics between the passes and the exact selector's logit cache.
  * Diagnostic: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
  * of ws holds, after the call and until ws is used again, the number of rows that had to be redone by the exact general selector
  * (cut outside the histogram window, or too many keys tied around the cut). */

@@ -127,7 +127,7 @@ gvote_status gvote_score_select(const gvote_shape *shape, const gvote_item *item
   }
   if (!aligned16(q) || (ws && !aligned16(ws))) return GVOTE_ERR_SHAPE;
   const size_t need = plan_score(shape, items, n_items, S).ws_bytes;
-  if (need > 0 && (!ws || ws_bytes < need)) return GVOTE_ERR_WORKSPACE;
+  if (!ws || ws_bytes < need) return GVOTE_ERR_WORKSPACE;
   return launch_score_select(shape, items, n_items, S, q, p, mode, k_per_row, rowmask, row_max, row_sum, ws,
                              ws_bytes, reinterpret_cast<hipStream_t>(stream));
 }

@@ -206,6 +206,9 @@ struct ScoreTable {
   const int *row_list;                 // null (every row of the batch), or the batch rows to process ...
   const int *n_list;                   // ... and how many there are (device side)
   int *n_fallback;                     // null, or counter incremented once per row this kernel processes
+  float *lg_cache;                     // null, or cache_rows slices of cache_stride floats (one per workgroup)
+  long long cache_stride;
+  int cache_rows, pad5;
   ScoreItem it[kMaxItems];
 };
 struct ScorePlan { size_t ws_bytes; };
@@ -268,7 +271,9 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
 gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
                                         const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
                                         long long mask_off0, float *row_max, float *row_sum, const int *row_list,
-                                        const int *n_list, int *n_fallback, hipStream_t st);
+                                        const int *n_list, int *n_fallback, float *lg_cache, size_t cache_bytes,
+                                        hipStream_t st);
+size_t general_cache_bytes(const gvote_item *items, int n_items);
 ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                  float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,

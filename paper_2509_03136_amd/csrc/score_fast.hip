@@ -979,7 +979,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     // rows the histogram could not settle are redone exactly
     gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, GVOTE_SELECT_TOPP, nullptr, rowmask,
                                                   batch_mask_off0, row_max, row_sum, tab.row_list, tab.n_list,
-                                                  tab.n_fallback, st);
+                                                  tab.n_fallback, reinterpret_cast<float *>(wsb + pl.ws_bytes),
+                                                  general_cache_bytes(items, n_items), st);
     if (stt != GVOTE_OK) return stt;
   }
   return GVOTE_OK;

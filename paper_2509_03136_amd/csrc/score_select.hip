@@ -15,6 +15,8 @@
 //               that reaches the target (ties are broken towards the lower position).
 // The logit of a key is computed by the same instruction sequence in every pass, so passes agree
 // bit for bit.
+#include <algorithm>
+
 #include "gvote_internal.hpp"
 
 namespace gvote {
@@ -36,7 +38,9 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u) {
 constexpr double kSelFix = 1099511627776.0;
 
 template <typename T>
-__device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow) {
+__device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow, float *cache) {
+  // `cache` (null or L floats of workspace owned by this workgroup): the row's logits, written by pass 0
+  // and re-read by the later passes instead of recomputing them; a thread only re-reads what it wrote.
   constexpr int NV = Vec16<T>::N;
   constexpr int NW = kSelThreads / 64;
   const int it = grow / tab.rows_per_item;
@@ -108,7 +112,10 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
   for (int tile0 = 0; tile0 < L; tile0 += kSelThreads) {
     fill_tile(tile0);
     __syncthreads();
-    if (tile0 + tid < L) m = fmaxf(m, lg[tid]);
+    if (tile0 + tid < L) {
+      m = fmaxf(m, lg[tid]);
+      if (cache) cache[tile0 + tid] = lg[tid];
+    }
     __syncthreads();
   }
   for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
@@ -131,10 +138,12 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
     __syncthreads();
     const uint32_t prefix = sh_prefix;
     for (int tile0 = 0; tile0 < L; tile0 += kSelThreads) {
-      fill_tile(tile0);
-      __syncthreads();
+      if (!cache) {
+        fill_tile(tile0);
+        __syncthreads();
+      }
       if (tile0 + tid < L) {
-        const float l = lg[tid];
+        const float l = cache ? cache[tile0 + tid] : lg[tid];
         const uint32_t u = ordered_bits(l);
         if (pass == 0 || (u >> (shift + 8)) == prefix) {
           const int dg = (u >> shift) & 255;
@@ -142,8 +151,9 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
           atomicAdd(&cnt[dg], 1);
         }
       }
-      __syncthreads();
+      if (!cache) __syncthreads();
     }
+    __syncthreads();
     if (pass == 0 && tid == 0) {
       double z = 0.0;
       for (int dg = 255; dg >= 0; --dg) z += (double)hist[dg];
@@ -199,7 +209,7 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
   const bool rank_ties = !keep_all && take < ties;
   for (int step = 0; step < n_steps; ++step) {
     const int t = step * kSelThreads + tid;
-    if (!keep_all) {
+    if (!keep_all && !cache) {
       fill_tile(step * kSelThreads);
       __syncthreads();
     }
@@ -208,7 +218,7 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
       if (keep_all) {
         sel = true;
       } else {
-        const uint32_t u = ordered_bits(lg[tid]);
+        const uint32_t u = ordered_bits(cache ? cache[t] : lg[tid]);
         sel = u > tau;
         tie = u == tau;
       }
@@ -242,35 +252,53 @@ __device__ __forceinline__ void select_row_body(const ScoreTable &tab, int grow)
 // grid: every row of the batch (row_list null), or a fixed number of workgroups walking the list
 template <typename T>
 __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const ScoreTable tab) {
+  // workgroup b may keep a row's logits in the b-th slice of the logit cache, if there is one for it
+  float *cache = (int)blockIdx.x < tab.cache_rows ? tab.lg_cache + (size_t)blockIdx.x * tab.cache_stride : nullptr;
   if (tab.row_list == nullptr) {
-    select_row_body<T>(tab, blockIdx.x);
+    select_row_body<T>(tab, blockIdx.x, cache);
     return;
   }
   const int n = *tab.n_list;
   for (int i = blockIdx.x; i < n; i += gridDim.x) {
-    select_row_body<T>(tab, tab.row_list[i]);
+    select_row_body<T>(tab, tab.row_list[i], cache);
     __syncthreads();
   }
 }
 
 }  // namespace
 
+// Logit cache of the general selector: room for kCacheRows rows of the longest item (rows beyond that
+// recompute their logits in every pass).
+constexpr int kCacheRows = 128;
+size_t general_cache_bytes(const gvote_item *items, int n_items) {
+  int max_L = 0;
+  for (int i = 0; i < n_items; ++i) max_L = items[i].L > max_L ? items[i].L : max_L;
+  return (size_t)kCacheRows * ((max_L + 63) / 64 * 64) * sizeof(float);
+}
+
 ScorePlan plan_score(const gvote_shape *sh, const gvote_item *items, int n_items, int S) {
   ScorePlan p;
-  p.ws_bytes = fast_path_ok(sh, S, GVOTE_SELECT_TOPP, 0.5f) ? plan_fast(sh, items, n_items, S).ws_bytes : 0;
+  p.ws_bytes = general_cache_bytes(items, n_items) + 256;
+  if (fast_path_ok(sh, S, GVOTE_SELECT_TOPP, 0.5f)) p.ws_bytes += plan_fast(sh, items, n_items, S).ws_bytes;
   return p;
 }
 
 gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
                                         const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,
                                         long long mask_off0, float *row_max, float *row_sum, const int *row_list,
-                                        const int *n_list, int *n_fallback, hipStream_t st) {
+                                        const int *n_list, int *n_fallback, float *lg_cache, size_t cache_bytes,
+                                        hipStream_t st) {
   ScoreTable tab;
   tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
   tab.head_dim = sh->head_dim; tab.mode = mode; tab.rows_per_item = S * sh->n_q_heads; tab.item0 = item0;
   tab.p = p; tab.pad2 = 0.f; tab.scale = 1.0 / sqrt((double)sh->head_dim);
   tab.q = q; tab.k_per_row = k_per_row; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
   tab.row_list = row_list; tab.n_list = n_list; tab.n_fallback = n_fallback;
+  int max_L = 0;
+  for (int i = 0; i < nb; ++i) max_L = items[i].L > max_L ? items[i].L : max_L;
+  tab.cache_stride = (max_L + 63) / 64 * 64;
+  tab.lg_cache = lg_cache;
+  tab.cache_rows = lg_cache ? (int)std::min<size_t>(cache_bytes / ((size_t)tab.cache_stride * sizeof(float)), 1 << 20) : 0;
   long long mask_off = mask_off0;
   for (int i = 0; i < nb; ++i) {
     const gvote_item &g = items[i];
@@ -297,10 +325,12 @@ gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items,
   for (int i = 0; i < n_items && fast; ++i) fast = items[i].L >= 32;   // the matrix-core path loads whole 32-key tiles
   if (fast) return launch_score_fast(sh, items, n_items, S, q, p, rowmask, row_max, row_sum, ws, st);
   long long mask_off = 0;
+  const size_t cache_bytes = ws ? general_cache_bytes(items, n_items) : 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
     const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
     const gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, mode, k_per_row, rowmask,
-                                                        mask_off, row_max, row_sum, nullptr, nullptr, nullptr, st);
+                                                        mask_off, row_max, row_sum, nullptr, nullptr, nullptr,
+                                                        reinterpret_cast<float *>(ws), cache_bytes, st);
     if (stt != GVOTE_OK) return stt;
     for (int i = 0; i < nb; ++i) mask_off += (long long)S * sh->n_q_heads * ((items[b0 + i].L + 31) / 32);
   }
