@@ -17,12 +17,16 @@ What is computed (one "item" = one request x one layer):
   top_p_select      Sec. 3.1: the minimal key set whose softmax mass reaches p
   union_vote        Step 4 / Alg. 1 "K = union of C^(s)", B = |K|
   compact           Alg. 1 "prune (K, V) to the indices in K", Sec. 3.4 (mask, nonzero, gather)
+  decode_attention  Eq. (1)-(2) of one decode query per head over the compressed, per-head cache (Sec. 3.4)
+  attention_overlap Sec. 3.3 "Attention Overlap": real-query attention mass on a synthetic query's set
 
 Pins (tests/test_oracle_pins.py, CPU only): Philox against the generator's
 published known-answer vectors; normals by distribution tests against SciPy's
 normal law; moments, RoPE, top-p by closed forms; top-p by brute-force subset
 enumeration; projection/scores by hand-built one-hot cases; union/compaction by
-set arithmetic on hand-written examples.  `gvote_item` (the composition, i.e.
+set arithmetic on hand-written examples; decode attention against SciPy's softmax
+and closed forms (equal keys -> mean of V, a dominant key -> its V); overlap by
+its bounds and the full-set / complement identities.  `gvote_item` (the composition, i.e.
 end-to-end budgets on synthetic inputs) has no printed value in the paper to
 compare with: parity unpinned for its budgets beyond the invariants the tests
 state (union >= every row set, monotone in p and S, p -> 1 keeps all).
@@ -36,7 +40,7 @@ __all__ = [
     "philox4x32_10", "philox_u32_stream", "uniform_from_u32", "standard_normals",
     "round_to_dtype", "fit_gaussian", "sample_hidden", "rope_cos_sin", "project_rope",
     "scores", "softmax_weights", "top_p_select", "top_k_select", "select_rows", "union_vote",
-    "compact", "pack_mask_words", "unpack_mask_words", "gvote_item",
+    "compact", "pack_mask_words", "unpack_mask_words", "gvote_item", "decode_attention", "attention_overlap",
 ]
 
 _M32 = np.uint64(0xFFFFFFFF)
@@ -297,6 +301,44 @@ def unpack_mask_words(words: np.ndarray, L: int) -> np.ndarray:
     w = np.asarray(words, dtype=np.uint32)
     bits = (w[..., :, None] >> np.arange(32, dtype=np.uint32)) & np.uint32(1)
     return bits.reshape(w.shape[:-1] + (-1,))[..., :L].astype(bool)
+
+
+# --------------------------------------------------------------------------
+# Consumer side: attention over the compressed cache, and the overlap diagnostic.
+# --------------------------------------------------------------------------
+def decode_attention(q, k_out, v_out, offsets, n_kv_heads: int):
+    """Eq. (1)-(2) on the non-uniform cache of Sec. 3.4: for query head h (KV head h div G) the output is
+    softmax(q[h] K_h^T / sqrt(d_k)) V_h over the rows offsets[h div G] .. offsets[h div G + 1] - 1 of the
+    packed cache.  q[H_q, d_k]; returns (out[H_q, d_k], lse[H_q]) in fp64, lse = log sum exp of the logits."""
+    q = np.asarray(q, dtype=np.float64)
+    hq, dk = q.shape
+    G = hq // n_kv_heads
+    out = np.zeros((hq, dk))
+    lse = np.zeros(hq)
+    for h in range(hq):
+        lo, hi = int(offsets[h // G]), int(offsets[h // G + 1])
+        kk = np.asarray(k_out[lo:hi], dtype=np.float64)
+        vv = np.asarray(v_out[lo:hi], dtype=np.float64)
+        l = kk @ q[h] / math.sqrt(dk)
+        m = l.max()
+        w = np.exp(l - m)
+        out[h] = (w / w.sum()) @ vv
+        lse[h] = m + math.log(w.sum())
+    return out, lse
+
+
+def attention_overlap(q_real, k, rowmask):
+    """Sec. 3.3: overlap[s, h] = sum over the keys of synthetic row (s, h)'s set of the attention weights
+    of the real query head h (softmax over all L keys).  q_real[H_q, d_k], k[L, H_kv, d_k], rowmask[S, H_q, L]."""
+    lg = scores(np.asarray(q_real, dtype=np.float64)[None], k)[0]          # [H_q, L]
+    S, hq, L = rowmask.shape
+    out = np.zeros((S, hq))
+    for h in range(hq):
+        _, w, Z = softmax_weights(lg[h])
+        a = w / Z
+        for s in range(S):
+            out[s, h] = a[rowmask[s, h]].sum()
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -358,6 +358,45 @@ def test_path_invariants_on_tiny_workload():
     assert np.array_equal(one["rowmask"][0, 0], O.top_p_select(lg[0, 0], 0.5))
 
 
+# ---------------------------------------------------------------- consumer side
+def test_decode_attention_closed_forms_and_scipy():
+    from scipy.special import softmax, logsumexp
+    rng = np.random.default_rng(6)
+    hq, hkv, dk = 4, 2, 8
+    offs = np.array([0, 5, 12])
+    k = rng.normal(size=(12, dk))
+    v = rng.normal(size=(12, dk))
+    q = rng.normal(size=(hq, dk))
+    out, lse = O.decode_attention(q, k, v, offs, hkv)
+    for h in range(hq):
+        lo, hi = offs[h // 2], offs[h // 2 + 1]
+        l = k[lo:hi] @ q[h] / math.sqrt(dk)
+        assert np.allclose(out[h], softmax(l) @ v[lo:hi]) and np.isclose(lse[h], logsumexp(l))
+    # equal keys -> plain mean of the head's values; a dominant key -> its value row
+    out, _ = O.decode_attention(q, np.ones_like(k), v, offs, hkv)
+    assert np.allclose(out[0], v[0:5].mean(0)) and np.allclose(out[3], v[5:12].mean(0))
+    kd = np.zeros_like(k)
+    kd[7] = 100.0 * q[2] / np.linalg.norm(q[2])
+    out, _ = O.decode_attention(q, kd, v, offs, hkv)
+    assert np.allclose(out[2], v[7], atol=1e-9)
+
+
+def test_attention_overlap_identities():
+    rng = np.random.default_rng(7)
+    S, hq, hkv, dk, L = 3, 4, 2, 8, 40
+    k = rng.normal(size=(L, hkv, dk))
+    q = rng.normal(size=(hq, dk))
+    rm = rng.random((S, hq, L)) < 0.3
+    ov = O.attention_overlap(q, k, rm)
+    assert np.all(ov >= 0) and np.all(ov <= 1 + 1e-12)
+    assert np.allclose(ov + O.attention_overlap(q, k, ~rm), 1.0)               # a set and its complement
+    assert np.allclose(O.attention_overlap(q, k, np.ones_like(rm)), 1.0)
+    # the real query's own top-p set overlaps itself by at least p
+    lg = O.scores(q[None], k)[0]
+    own = np.stack([O.top_p_select(lg[h], 0.9) for h in range(hq)])[None]
+    assert np.all(O.attention_overlap(q, k, own) >= 0.9 - 1e-12)
+
+
 # ---------------------------------------------------------------- test infrastructure itself
 def test_band_sets_bracket_the_oracle_selection():
     import sys
