@@ -179,6 +179,23 @@ GVOTE_API gvote_status gvote_union_compact(const gvote_shape *shape, const gvote
 GVOTE_API gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
                                         const uint32_t *rowmask, int32_t repeat, int32_t *counts, void *stream);
 
+/* Consumer of the compressed cache (Sec. 3.4: a non-uniform per-head cache behind a variable-length
+ * attention interface; Eq. (1)-(2)).  One decode query per item and head: q[n_items, n_q_heads, head_dim]
+ * (dtype); head h of item i attends to rows offsets[i*n_kv_heads + h/G] .. offsets[.. + 1] - 1 of the packed
+ * k_out / v_out that gvote_union_compact produced:  out[i, h, :] = softmax(q K^T / sqrt(head_dim)) V, rounded
+ * to dtype ([n_items, n_q_heads, head_dim]); lse[i, h] (fp32, optional) = log sum exp of the logits.
+ * head_dim * element size / 16 must be a power of two <= 64 (else GVOTE_ERR_UNSUPPORTED). */
+GVOTE_API gvote_status gvote_decode_attention(const gvote_shape *shape, int32_t n_items, const void *q,
+                                              const void *k_out, const void *v_out, const int64_t *offsets,
+                                              void *out, float *lse, void *stream);
+
+/* Sec. 3.3 "Attention Overlap": overlap[i, s, h] (fp32, [n_items, S, n_q_heads]) = the share of the REAL query
+ * q_real[i, h, :]'s attention (softmax over all L keys of KV head h/G) that falls on the keys selected in row
+ * (s, h) of rowmask.  q_real [n_items, n_q_heads, head_dim] (dtype).  ws: gvote_workspace_bytes. */
+GVOTE_API gvote_status gvote_attention_overlap(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
+                                               int32_t S, const void *q_real, const uint32_t *rowmask,
+                                               float *overlap, void *ws, size_t ws_bytes, void *stream);
+
 /* Test aid: out[e] (device uint32, e < n) = Philox4x32-10 draw e of stream (seed, stream_id),
  * the integer stream gvote_sample_queries consumes. */
 GVOTE_API gvote_status gvote_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, void *stream);

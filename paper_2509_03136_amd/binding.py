@@ -67,6 +67,10 @@ def lib() -> C.CDLL:
     L.gvote_union_compact.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     L.gvote_count_rows.restype = C.c_int
     L.gvote_count_rows.argtypes = [sp, ip, i32, i32, vp, i32, vp, vp]
+    L.gvote_decode_attention.restype = C.c_int
+    L.gvote_decode_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.gvote_attention_overlap.restype = C.c_int
+    L.gvote_attention_overlap.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, sz, vp]
     L.gvote_philox_u32.restype = C.c_int
     L.gvote_philox_u32.argtypes = [u64, u64, i64, vp, vp]
     _lib = L
@@ -174,6 +178,19 @@ def union_compact(b: Batch, S: int, rowmask: torch.Tensor, union_mask: torch.Ten
 def count_rows(b: Batch, S: int, rowmask: torch.Tensor, repeat: int, counts: torch.Tensor, stream=None) -> None:
     _check(lib().gvote_count_rows(C.byref(b.shape), b.items, b.n_items, S, _ptr(rowmask), int(repeat), _ptr(counts),
                                   _stream(stream)), "gvote_count_rows")
+
+
+def decode_attention(b: Batch, q: torch.Tensor, k_out: torch.Tensor, v_out: torch.Tensor, offsets: torch.Tensor,
+                     out: torch.Tensor, lse: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(lib().gvote_decode_attention(C.byref(b.shape), b.n_items, _ptr(q), _ptr(k_out), _ptr(v_out), _ptr(offsets),
+                                        _ptr(out), _ptr(lse), _stream(stream)), "gvote_decode_attention")
+
+
+def attention_overlap(b: Batch, S: int, q_real: torch.Tensor, rowmask: torch.Tensor, overlap: torch.Tensor,
+                      ws: torch.Tensor, stream=None) -> None:
+    _check(lib().gvote_attention_overlap(C.byref(b.shape), b.items, b.n_items, S, _ptr(q_real), _ptr(rowmask),
+                                         _ptr(overlap), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "gvote_attention_overlap")
 
 
 def philox_u32(seed: int, stream_id: int, n: int, out: torch.Tensor, stream=None) -> None:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgvote.so")
-SOURCES = ["gvote_api.cpp", "fit_gaussian.hip", "sample_queries.hip", "score_select.hip", "score_fast.hip", "union_compact.hip"]
+SOURCES = ["gvote_api.cpp", "fit_gaussian.hip", "sample_queries.hip", "score_select.hip", "score_fast.hip", "union_compact.hip", "consumer.hip"]
 
 
 def build(verbose: bool = True, out: str = LIB, extra=()) -> str:

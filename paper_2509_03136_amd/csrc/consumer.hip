@@ -1,0 +1,269 @@
+// Consumer side of the compressed cache (paper Sec. 3.4: a non-uniform, per-head cache read through a
+// variable-length attention interface; Eq. (1)-(2)), and the attention-overlap diagnostic of Sec. 3.3.
+//
+//   decode_attention   one decode query per head against the packed rows of its KV head:
+//                      softmax(q K^T / sqrt(d_k)) V.  One workgroup per (item, KV head) serves the G query
+//                      heads of the group, so every packed K/V row is read once; rows are contiguous in
+//                      the packed cache: a key row is read by d_k*elem/16 neighbouring lanes, 16 bytes each;
+//                      online softmax per lane group, merged across the wave by shuffles and across the
+//                      workgroup through LDS.  Memory-bound (2 * B * d_k * elem bytes per KV head).
+//   attention_overlap  how much of a REAL query's attention falls on the key set a synthetic row chose:
+//                      per (item, query head) the real query's logits over all L keys (kept in the
+//                      workspace), their softmax, and for every sample s the weight inside row (s, h)'s mask.
+#include "gvote_internal.hpp"
+
+namespace gvote {
+
+namespace {
+
+constexpr int kGMax = 8;    // query heads of a group handled per sweep over the packed rows
+
+struct DecodeArgs {
+  const void *q, *k_out, *v_out;
+  const long long *offsets;
+  void *out;
+  float *lse;
+  int n_q_heads, n_kv_heads, head_dim;
+  float scale;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs a) {
+  constexpr int NV = Vec16<T>::N;
+  const int dk = a.head_dim;
+  const int ppr = dk / NV;                       // lanes per row (power of two, <= 64: checked by the host)
+  const int rps = 64 / ppr;                      // rows per wave step
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int piece = lane % ppr, rs = lane / ppr;
+  const int hh = blockIdx.x;                     // item * H_kv + kv head
+  const int item = hh / a.n_kv_heads, kvh = hh - item * a.n_kv_heads;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const long long lo = a.offsets[hh], hi = a.offsets[hh + 1];
+  const T *kb = reinterpret_cast<const T *>(a.k_out);
+  const T *vb = reinterpret_cast<const T *>(a.v_out);
+  __shared__ float part[4][kGMax][256 + 2];      // per wave: acc[d_k], m, l of every head of the sweep
+
+  for (int g0 = 0; g0 < G; g0 += kGMax) {
+    const int ng = min(kGMax, G - g0);
+    float qv[kGMax][NV], m[kGMax], l[kGMax], acc[kGMax][NV];
+#pragma unroll
+    for (int g = 0; g < kGMax; ++g) {
+      m[g] = -INFINITY;
+      l[g] = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) { acc[g][i] = 0.f; qv[g][i] = 0.f; }
+      if (g < ng) {
+        const T *qrow = reinterpret_cast<const T *>(a.q) + ((size_t)item * a.n_q_heads + kvh * G + g0 + g) * dk;
+        Vec16<T>::load(qrow + piece * NV, qv[g]);
+      }
+    }
+    for (long long r0 = lo + (long long)wave * rps; r0 < hi; r0 += 4 * rps) {
+      const long long r = r0 + rs;
+      const bool valid = r < hi;
+      const long long rc = valid ? r : hi - 1;   // in bounds; the contribution is dropped
+      float kv[NV], vv[NV];
+      Vec16<T>::load(kb + rc * dk + piece * NV, kv);
+      Vec16<T>::load(vb + rc * dk + piece * NV, vv);
+#pragma unroll
+      for (int g = 0; g < kGMax; ++g) {
+        if (g < ng) {
+          float s = 0.f;
+#pragma unroll
+          for (int i = 0; i < NV; ++i) s = fmaf(qv[g][i], kv[i], s);
+          for (int off = ppr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+          s *= a.scale;
+          if (valid) {
+            const float mn = fmaxf(m[g], s);
+            const float corr = expf(m[g] - mn), pw = expf(s - mn);     // expf(-inf) = 0 on the first row
+            l[g] = l[g] * corr + pw;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) acc[g][i] = fmaf(acc[g][i], corr, pw * vv[i]);
+            m[g] = mn;
+          }
+        }
+      }
+    }
+    // merge the row slots of the wave (lanes with the same piece), then the four waves
+#pragma unroll
+    for (int g = 0; g < kGMax; ++g) {
+      if (g < ng) {
+        for (int off = ppr; off < 64; off <<= 1) {
+          const float mo = __shfl_xor(m[g], off, 64), lo2 = __shfl_xor(l[g], off, 64);
+          const float mn = fmaxf(m[g], mo);
+          const float ca = mn == -INFINITY ? 0.f : expf(m[g] - mn), cb = mn == -INFINITY ? 0.f : expf(mo - mn);
+          l[g] = l[g] * ca + lo2 * cb;
+#pragma unroll
+          for (int i = 0; i < NV; ++i) acc[g][i] = acc[g][i] * ca + __shfl_xor(acc[g][i], off, 64) * cb;
+          m[g] = mn;
+        }
+        if (rs == 0) {
+#pragma unroll
+          for (int i = 0; i < NV; ++i) part[wave][g][piece * NV + i] = acc[g][i];
+          if (piece == 0) { part[wave][g][256] = m[g]; part[wave][g][257] = l[g]; }
+        }
+      }
+    }
+    __syncthreads();
+    for (int o = threadIdx.x; o < ng * dk; o += 256) {
+      const int g = o / dk, ch = o - g * dk;
+      float mn = -INFINITY;
+      for (int w = 0; w < 4; ++w) mn = fmaxf(mn, part[w][g][256]);
+      float num = 0.f, den = 0.f;
+      for (int w = 0; w < 4; ++w) {
+        const float cw = part[w][g][256] == -INFINITY ? 0.f : expf(part[w][g][256] - mn);
+        num = fmaf(part[w][g][ch], cw, num);
+        den = fmaf(part[w][g][257], cw, den);
+      }
+      const size_t row = (size_t)item * a.n_q_heads + kvh * G + g0 + g;
+      reinterpret_cast<T *>(a.out)[row * dk + ch] = from_f32<T>(den > 0.f ? num / den : 0.f);
+      if (ch == 0 && a.lse) a.lse[row] = den > 0.f ? mn + logf(den) : -INFINITY;
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------- attention overlap
+struct OverlapItem {
+  const void *k;
+  long long tok_stride, head_stride, mask_off, cache_off;
+  int L, W;
+};
+struct OverlapTable {
+  int n_items, S, n_q_heads, n_kv_heads, head_dim, item0;
+  double scale;
+  const void *q_real;          // [n_items_call][H_q][d_k]
+  const uint32_t *rowmask;
+  float *overlap;              // [n_items_call][S][H_q]
+  float *cache;                // workspace: the real query's logits, one slice per (item, head)
+  OverlapItem it[kMaxItems];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void attention_overlap_kernel(const OverlapTable tab) {
+  constexpr int NV = Vec16<T>::N;
+  typedef typename Acc<T>::type acc_t;
+  const int it = blockIdx.x / tab.n_q_heads, h = blockIdx.x - it * tab.n_q_heads;
+  const OverlapItem I = tab.it[it];
+  const int kvh = h / (tab.n_q_heads / tab.n_kv_heads);
+  const int dk = tab.head_dim, L = I.L;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ float q_s[256];
+  __shared__ float red[4];
+  const T *qrow = reinterpret_cast<const T *>(tab.q_real) + ((size_t)(tab.item0 + it) * tab.n_q_heads + h) * dk;
+  if (tid < dk) q_s[tid] = to_f32<T>(qrow[tid]);
+  __syncthreads();
+  float *cache = tab.cache + I.cache_off + (long long)h * ((L + 63) / 64 * 64);
+  const T *kbase = reinterpret_cast<const T *>(I.k) + (long long)kvh * I.head_stride;
+  const int ppr = dk / NV;
+  int lpk = 1;
+  while (lpk < ppr) lpk <<= 1;
+  const int kpi = 256 / lpk, slot = tid / lpk, piece = tid - slot * lpk;
+  auto block_max = [&](float v) {
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    v = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    return v;
+  };
+  auto block_sum = [&](float v) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    v = red[0] + red[1] + red[2] + red[3];
+    __syncthreads();
+    return v;
+  };
+  // logits of the real query (a key row is read by lpk neighbouring lanes), kept in the workspace
+  float m = -INFINITY;
+  for (int t0 = 0; t0 < L; t0 += kpi) {
+    const int t = t0 + slot;
+    acc_t acc = 0;
+    if (piece < ppr && t < L) {
+      float kv[NV];
+      Vec16<T>::load(kbase + (long long)t * I.tok_stride + piece * NV, kv);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) acc = fma((acc_t)q_s[piece * NV + i], (acc_t)kv[i], acc);
+    }
+    for (int off = lpk >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (piece == 0 && t < L) {
+      const float lg = (float)(acc * (acc_t)tab.scale);
+      cache[t] = lg;
+      m = fmaxf(m, lg);
+    }
+  }
+  m = block_max(m);
+  __threadfence_block();
+  __syncthreads();
+  float z = 0.f;
+  for (int t = tid; t < L; t += 256) z += expf(cache[t] - m);
+  z = block_sum(z);
+  for (int s = 0; s < tab.S; ++s) {
+    const uint32_t *mrow = tab.rowmask + I.mask_off + (long long)(s * tab.n_q_heads + h) * I.W;
+    float w = 0.f;
+    for (int t = tid; t < L; t += 256)
+      if ((mrow[t >> 5] >> (t & 31)) & 1u) w += expf(cache[t] - m);
+    w = block_sum(w);
+    if (tid == 0) tab.overlap[((size_t)(tab.item0 + it) * tab.S + s) * tab.n_q_heads + h] = w / z;
+  }
+}
+
+}  // namespace
+
+size_t overlap_ws_bytes(const gvote_shape *sh, const gvote_item *items, int n_items) {
+  size_t worst = 0;
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    size_t f = 0;
+    for (int i = 0; i < nb; ++i) f += (size_t)sh->n_q_heads * ((items[b0 + i].L + 63) / 64 * 64);
+    if (f > worst) worst = f;
+  }
+  return worst * sizeof(float);
+}
+
+gvote_status launch_decode_attention(const gvote_shape *sh, int n_items, const void *q, const void *k_out,
+                                     const void *v_out, const long long *offsets, void *out, float *lse,
+                                     hipStream_t st) {
+  DecodeArgs a;
+  a.q = q; a.k_out = k_out; a.v_out = v_out; a.offsets = offsets; a.out = out; a.lse = lse;
+  a.n_q_heads = sh->n_q_heads; a.n_kv_heads = sh->n_kv_heads; a.head_dim = sh->head_dim;
+  a.scale = (float)(1.0 / sqrt((double)sh->head_dim));
+  const dim3 grid(n_items * sh->n_kv_heads);
+  if (sh->dtype == GVOTE_F32)
+    hipLaunchKernelGGL(decode_attention_kernel<float>, grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(decode_attention_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+  GVOTE_CHECK_LAUNCH();
+  return GVOTE_OK;
+}
+
+gvote_status launch_attention_overlap(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
+                                      const void *q_real, const uint32_t *rowmask, float *overlap, void *ws,
+                                      hipStream_t st) {
+  long long mask_off = 0;
+  for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {
+    const int nb = n_items - b0 < kMaxItems ? n_items - b0 : kMaxItems;
+    OverlapTable tab;
+    tab.n_items = nb; tab.S = S; tab.n_q_heads = sh->n_q_heads; tab.n_kv_heads = sh->n_kv_heads;
+    tab.head_dim = sh->head_dim; tab.item0 = b0; tab.scale = 1.0 / sqrt((double)sh->head_dim);
+    tab.q_real = q_real; tab.rowmask = rowmask; tab.overlap = overlap; tab.cache = reinterpret_cast<float *>(ws);
+    long long cache_off = 0;
+    for (int i = 0; i < nb; ++i) {
+      const gvote_item &g = items[b0 + i];
+      OverlapItem &o = tab.it[i];
+      o.k = g.k; o.tok_stride = g.kv_tok_stride; o.head_stride = g.kv_head_stride;
+      o.L = g.L; o.W = (g.L + 31) / 32; o.mask_off = mask_off; o.cache_off = cache_off;
+      mask_off += (long long)S * sh->n_q_heads * o.W;
+      cache_off += (long long)sh->n_q_heads * ((g.L + 63) / 64 * 64);
+    }
+    const dim3 grid(nb * sh->n_q_heads);
+    if (sh->dtype == GVOTE_F32)
+      hipLaunchKernelGGL(attention_overlap_kernel<float>, grid, dim3(256), 0, st, tab);
+    else
+      hipLaunchKernelGGL(attention_overlap_kernel<bf16_t>, grid, dim3(256), 0, st, tab);
+    GVOTE_CHECK_LAUNCH();
+  }
+  return GVOTE_OK;
+}
+
+}  // namespace gvote

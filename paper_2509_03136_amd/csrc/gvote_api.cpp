@@ -55,6 +55,7 @@ size_t workspace_bytes_unchecked(const gvote_shape *sh, const gvote_item *items,
   w = max_sz(w, plan_sample(sh, n_items, S).ws_bytes);
   w = max_sz(w, plan_score(sh, items, n_items, S).ws_bytes);
   w = max_sz(w, plan_union(sh, items, n_items).ws_bytes);
+  w = max_sz(w, overlap_ws_bytes(sh, items, n_items));
   return align_up(w, 256) + 256;
 }
 
@@ -158,6 +159,32 @@ gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items,
   if (!rowmask || !counts || S < 1 || repeat < 1) return GVOTE_ERR_INVALID_ARG;
   if (S > 128) return GVOTE_ERR_CAPACITY;
   return launch_count_rows(shape, items, n_items, S, rowmask, repeat, counts, reinterpret_cast<hipStream_t>(stream));
+}
+
+gvote_status gvote_decode_attention(const gvote_shape *shape, int32_t n_items, const void *q, const void *k_out,
+                                    const void *v_out, const int64_t *offsets, void *out, float *lse, void *stream) {
+  gvote_status st = check_shape(shape);
+  if (st != GVOTE_OK) return st;
+  if (n_items < 1 || !q || !k_out || !v_out || !offsets || !out) return GVOTE_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_out) || !aligned16(v_out) || !aligned16(out)) return GVOTE_ERR_SHAPE;
+  const int ppr = shape->head_dim * (int)elem_bytes(shape->dtype) / 16;
+  if (ppr < 1 || ppr > 64 || (ppr & (ppr - 1))) return GVOTE_ERR_UNSUPPORTED;
+  return launch_decode_attention(shape, n_items, q, k_out, v_out, reinterpret_cast<const long long *>(offsets), out,
+                                 lse, reinterpret_cast<hipStream_t>(stream));
+}
+
+gvote_status gvote_attention_overlap(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
+                                     const void *q_real, const uint32_t *rowmask, float *overlap, void *ws,
+                                     size_t ws_bytes, void *stream) {
+  gvote_status st = check_shape(shape);
+  if (st != GVOTE_OK) return st;
+  if ((st = check_items(shape, items, n_items, NEED_K)) != GVOTE_OK) return st;
+  if (!q_real || !rowmask || !overlap || !ws || S < 1) return GVOTE_ERR_INVALID_ARG;
+  if (S > 128) return GVOTE_ERR_CAPACITY;
+  if (!aligned16(q_real) || !aligned16(ws)) return GVOTE_ERR_SHAPE;
+  if (ws_bytes < overlap_ws_bytes(shape, items, n_items)) return GVOTE_ERR_WORKSPACE;
+  return launch_attention_overlap(shape, items, n_items, S, q_real, rowmask, overlap, ws,
+                                  reinterpret_cast<hipStream_t>(stream));
 }
 
 gvote_status gvote_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, void *stream) {

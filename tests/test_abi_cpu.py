@@ -27,7 +27,7 @@ def test_header_symbols_are_exported(g):
     names = declared_symbols()
     assert {"gvote_fit_gaussian", "gvote_sample_queries", "gvote_score_select", "gvote_union_compact",
             "gvote_workspace_bytes", "gvote_status_string", "gvote_abi_version", "gvote_philox_u32",
-            "gvote_count_rows"} <= set(names)
+            "gvote_count_rows", "gvote_decode_attention", "gvote_attention_overlap"} <= set(names)
     lib = C.CDLL(g.lib_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -116,6 +116,13 @@ def test_bad_arguments_are_rejected_before_any_launch(g):
                None) == WS
     assert L.gvote_count_rows(C.byref(sh), it, 1, 1, None, 8, 0x100, None) == INVALID
     assert L.gvote_count_rows(C.byref(sh), it, 1, 1, 0x100, 0, 0x200, None) == INVALID
+    dec = L.gvote_decode_attention
+    assert dec(C.byref(sh), 1, None, 0x100, 0x200, 0x300, 0x400, None, None) == INVALID
+    assert dec(C.byref(sh), 0, 0x100, 0x100, 0x200, 0x300, 0x400, None, None) == INVALID
+    assert dec(C.byref(_shape(g, head_dim=24)), 1, 0x100, 0x100, 0x200, 0x300, 0x400, None, None) == UNSUP
+    ovl = L.gvote_attention_overlap
+    assert ovl(C.byref(sh), it, 1, 8, None, 0x100, 0x200, ws, wsn, None) == INVALID
+    assert ovl(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, ws, 8, None) == WS
     assert L.gvote_philox_u32(1, 2, -1, None, None) == INVALID
     assert L.gvote_philox_u32(1, 2, 0, None, None) == 0
 
