@@ -88,7 +88,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by item with no communication, see DESIGN.md)", file=sys.stderr)
+              "(items are independent: more GPUs would each take a share of the items, with no communication)", file=sys.stderr)
         sys.exit(2)
 
     import torch
