@@ -137,6 +137,12 @@ class Batch:
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
         self.device = first["hidden"].device
 
+    @classmethod
+    def from_workload(cls, wl, items: Sequence[Dict], **kw) -> "Batch":
+        """Descriptors for the items of a synthetic workload (synth.workloads.Workload: geometry fields only)."""
+        return cls(items, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.d_k,
+                   rope_theta=wl.theta, n_skip=wl.n_skip, **kw)
+
     def words(self, i: int) -> int:
         return (self.lengths[i] + 31) // 32
 

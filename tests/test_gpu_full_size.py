@@ -1,11 +1,18 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
 uses (inputs generated on the device, all items in one batch).  The oracle cannot redo whole stacks in
-a test's time, so it recomputes SAMPLED outputs (chosen items / query rows, end to end from the same
+a test's time, so it recomputes SAMPLED outputs (chosen items / KV groups / query rows from the same
 stored inputs) and the rest is checked through properties that hold at any size: the union is the OR of
 the row masks, budgets are its popcounts, offsets their prefix sums, the packed cache is the rows the
-union names, in order."""
-import sys
+union names, in order.
 
+Two comparisons per sampled item:
+  own   the oracle scores the GPU's OWN stored synthetic queries (so only the accumulation arithmetic of
+        the score / selection stage differs): the full sandwich C(p - tol) <= C_gpu <= C(p + tol) at
+        STAGE_TOL, and the unions / budgets that follow from those rows;
+  e2e   the oracle runs the item end to end from the hidden states (its queries differ from the GPU's by
+        bf16 rounding flips): cumulative-mass band at TOL, validity of every GPU row on the oracle's
+        weights (reaches the mass, minimal, prefix of the logit order), budgets within 2 % + 8 keys.
+Boundary keys (|C_gpu xor C(p)|) are printed per configuration."""
 import numpy as np
 import pytest
 import torch
@@ -40,6 +47,7 @@ def _run(g, wl):
     pipe.select()
     torch.cuda.synchronize()
     pipe.n_fallback = pipe.fallback_rows()      # lives in the workspace: read before the next stage reuses it
+    pipe.fallback_why = pipe.fallback_reasons()
     pipe.compact()
     torch.cuda.synchronize()
     return items, pipe
@@ -73,34 +81,45 @@ def _structure_checks(wl, items, pipe, sample_items):
     return moff
 
 
-def _oracle_rows(wl, it, rows):
-    """Oracle logits of the sampled query rows of one item, from the item's stored inputs."""
-    cpu = {k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in it.items()}
-    r = U.oracle_item(wl, cpu, upto="q")
-    k = U.f32np(cpu["k"]).astype(np.float64)
-    G = wl.group
-    out = {}
-    for (s, h) in rows:
-        out[(s, h)] = k[:, h // G, :] @ r["q_tilde"][s, h] / np.sqrt(wl.d_k)
-    return r, out
+def _cpu(it):
+    return {k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in it.items()}
 
 
-def _check_sampled_rows(wl, it, pipe, item_index, moff, rows):
-    L = wl.lengths[item_index]
-    ref, lg = _oracle_rows(wl, it, rows)
-    gm = U.unpack_rows(pipe.rowmask[moff[item_index]:moff[item_index + 1]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
-    tol, p = U.TOL[wl.dtype], U.p32(wl.p)
-    boundary = 0
-    for (s, h), l in lg.items():
-        must, may = U.band_sets(l, p, tol)
-        got = gm[s, h]
-        assert not (must & ~got).any() and not (got & ~may).any(), (item_index, s, h)
-        boundary += int((got ^ O.top_p_select(l, p)).sum())
-        m = l.max()
-        assert abs(float(pipe.row_max[item_index, s * wl.n_q_heads + h]) - m) <= tol * (1 + abs(m))
-    mu = pipe.mu[item_index].cpu().numpy()
+def _check_item(wl, it, pipe, i, moff, kv_heads=None, samples=None):
+    """Both comparisons for item i, restricted to the KV heads `kv_heads` (all by default) and the samples
+    `samples` (all by default).  With every sample present the budgets of those heads are compared too.
+    Returns (boundary keys own, boundary keys e2e)."""
+    L, G = wl.lengths[i], wl.group
+    cpu = _cpu(it)
+    ref = U.oracle_item(wl, cpu, upto="q")
+    mu = pipe.mu[i].cpu().numpy()
     assert np.all(np.abs(mu - ref["mu"]) <= 1e-5 * np.maximum(np.abs(ref["mu"]), np.sqrt(ref["var"])) + 1e-7)
-    return boundary
+    kv_heads = list(range(wl.n_kv_heads)) if kv_heads is None else list(kv_heads)
+    ss = list(range(wl.S)) if samples is None else list(samples)
+    k = U.f32np(cpu["k"])
+    q_own = U.f32np(pipe.q[i]).astype(np.float64)
+    gm_all = U.unpack_rows(pipe.rowmask[moff[i]:moff[i + 1]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
+    p = U.p32(wl.p)
+    b_own = b_e2e = 0
+    for kvh in kv_heads:
+        heads = list(range(kvh * G, (kvh + 1) * G))
+        gm = gm_all[ss][:, heads]
+        kk = k[:, kvh:kvh + 1, :]
+        lg_own = O.scores(q_own[ss][:, heads], kk)
+        b_own += U.check_rowmask_strict(gm, lg_own, p, U.STAGE_TOL[wl.dtype])
+        lg_e2e = O.scores(ref["q_tilde"][ss][:, heads], kk)
+        b_e2e += U.check_rowmask_sandwich(gm, lg_e2e, p, U.TOL[wl.dtype])
+        m = lg_e2e.max(-1)
+        gmax = pipe.row_max[i].cpu().numpy().reshape(wl.S, wl.n_q_heads)[ss][:, heads]
+        assert np.all(np.abs(gmax - m) <= U.TOL[wl.dtype] * (1 + np.abs(m)))
+        if samples is None:
+            gb = int(pipe.budget[i, kvh].item())
+            own_b = int(O.union_vote(O.select_rows(lg_own, p), 1)[1][0])
+            e2e_b = int(O.union_vote(O.select_rows(lg_e2e, p), 1)[1][0])
+            say(f"    item {i} head {kvh}: budget gpu {gb}, oracle on the GPU's queries {own_b}, oracle end to end {e2e_b}")
+            assert abs(gb - own_b) <= 2, (gb, own_b)
+            U.check_budgets([gb], [e2e_b])
+    return b_own, b_e2e
 
 
 def test_config3_full_stack(g):
@@ -109,31 +128,29 @@ def test_config3_full_stack(g):
     items, pipe = _run(g, wl)
     moff = _structure_checks(wl, items, pipe, sample_items=(0, 17))
     assert pipe.n_fallback <= 8
-    # two layers end to end against the oracle
-    boundary = 0
-    for i in (5, 31):
-        cpu = {k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in items[i].items()}
-        ref = U.oracle_item(wl, cpu)
-        L = wl.lengths[i]
-        gm = U.unpack_rows(pipe.rowmask[moff[i]:moff[i + 1]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
-        boundary += U.check_rowmask_sandwich(gm, ref["logits"], U.p32(wl.p), U.TOL[wl.dtype])
-        gb = pipe.budget[i].cpu().numpy()
-        say(f"  layer {i}: budget gpu {gb.tolist()} oracle {ref['budget'].tolist()}")
-        assert np.all(np.abs(gb - ref["budget"]) <= 0.02 * ref["budget"] + 8)
+    own = e2e = 0
+    for i in (5, 31):                           # two whole layers against the oracle
+        a, b = _check_item(wl, items[i], pipe, i, moff)
+        own, e2e = own + a, e2e + b
     rho = float(pipe.offsets[-1].item()) / (sum(wl.lengths) * wl.n_kv_heads)
-    say(f"  boundary keys {boundary}, kept fraction {rho:.4f}, compressed bytes {int(pipe.offsets[-1].item()) * wl.d_k * 4}")
+    say(f"  boundary keys: {own} on the GPU's own queries, {e2e} end to end (2 layers = 1024 rows); kept fraction {rho:.4f}, "
+        f"compressed bytes {int(pipe.offsets[-1].item()) * wl.d_k * 4}, fallback rows {pipe.n_fallback} {pipe.fallback_why}")
+    assert own <= 8
 
 
-def test_config4_long_context_sampled_rows(g):
+def test_config4_long_context_whole_kv_group(g):
     wl = W.config(4)
     say("cfg4 full: 28 layers x 131072, S=32, G=7")
     items, pipe = _run(g, wl)
     moff = _structure_checks(wl, items, pipe, sample_items=(3,))
-    rows = [(0, 0), (5, 6), (13, 7), (31, 27), (17, 20), (8, 13)]
-    boundary = _check_sampled_rows(wl, items[9], pipe, 9, moff, rows)
-    boundary += _check_sampled_rows(wl, items[27], pipe, 27, moff, rows[:3])
+    # one whole KV group (224 rows x 131072 keys) of one layer, budgets included; sampled rows of two more layers
+    own, e2e = _check_item(wl, items[9], pipe, 9, moff, kv_heads=(2,))
+    for i, kvh, ss in ((27, 0, (0, 13, 31)), (14, 3, (5, 17))):
+        a, b = _check_item(wl, items[i], pipe, i, moff, kv_heads=(kvh,), samples=ss)
+        own, e2e = own + a, e2e + b
     rho = float(pipe.offsets[-1].item()) / (sum(wl.lengths) * wl.n_kv_heads)
-    say(f"  boundary keys {boundary}, kept fraction {rho:.4f}, fallback rows {pipe.n_fallback}")
+    say(f"  boundary keys: {own} own, {e2e} end to end (259 rows); kept fraction {rho:.4f}, fallback rows {pipe.n_fallback} {pipe.fallback_why}")
+    assert own <= 8
 
 
 def test_config5_ragged_batch(g):
@@ -142,14 +159,13 @@ def test_config5_ragged_batch(g):
     items, pipe = _run(g, wl)
     moff = _structure_checks(wl, items, pipe, sample_items=(0, 7, 15))
     shortest, longest = int(np.argmin(wl.lengths)), int(np.argmax(wl.lengths))
-    boundary = 0
-    for i in (shortest, 4):
-        cpu = {k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in items[i].items()}
-        ref = U.oracle_item(wl, cpu)
-        L = wl.lengths[i]
-        gm = U.unpack_rows(pipe.rowmask[moff[i]:moff[i + 1]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
-        boundary += U.check_rowmask_sandwich(gm, ref["logits"], U.p32(wl.p), U.TOL[wl.dtype])
-    boundary += _check_sampled_rows(wl, items[longest], pipe, longest, moff, [(0, 0), (7, 13), (15, 31)])
+    own = e2e = 0
+    for i in (shortest, 4):                     # two whole requests (request 4 holds the diagnosed near-tie)
+        a, b = _check_item(wl, items[i], pipe, i, moff)
+        own, e2e = own + a, e2e + b
+    a, b = _check_item(wl, items[longest], pipe, longest, moff, kv_heads=(0, 5), samples=(0, 7, 15))
+    own, e2e = own + a, e2e + b
     usage = pipe.budget.cpu().numpy().sum(1) / (np.array(wl.lengths) * wl.n_kv_heads)
-    say("  boundary keys", boundary, "usage per request", np.round(usage, 3).tolist())
+    say(f"  boundary keys: {own} own, {e2e} end to end; fallback rows {pipe.n_fallback}; usage per request", np.round(usage, 3).tolist())
+    assert own <= 8
     assert usage.max() > 2 * usage.min()          # the adaptive budgets really differ across requests

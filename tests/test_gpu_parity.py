@@ -1,6 +1,9 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
-Integer / byte / index work is bit-exact; floating point within the tolerance of parity_util.TOL;
-masks via the sandwich C(p - tol) <= gpu <= C(p + tol) with the boundary keys counted."""
+Integer / byte / index work is bit-exact; floating point within the tolerance of parity_util.TOL.
+Masks: where the stage is fed the oracle's own stored queries, the full sandwich
+C(p - tol) <= gpu <= C(p + tol) at STAGE_TOL (check_rowmask_strict); end to end (each side on its own
+queries) the cumulative-mass band plus the selection's validity on the oracle's weights and the budgets
+within 2 % + 8 keys (check_rowmask_sandwich, check_budgets).  Boundary keys are counted and printed."""
 import math
 import sys
 
@@ -173,7 +176,7 @@ def test_score_select_given_oracle_queries(g, name):
         off += n
         # same stored inputs on both sides: only fp32-vs-fp64 arithmetic separates them
         stol = U.STAGE_TOL[wl.dtype]
-        total_boundary += U.check_rowmask_sandwich(gm, r["logits"], U.p32(wl.p), stol)
+        total_boundary += U.check_rowmask_strict(gm, r["logits"], U.p32(wl.p), stol)
         m = r["logits"].max(-1)
         Z = np.exp(r["logits"] - m[..., None]).sum(-1)
         gmax = pipe.row_max[i].cpu().numpy().reshape(wl.S, wl.n_q_heads)
@@ -218,7 +221,7 @@ def test_select_degenerate_cases(g):
     itd = dict(it, k=kd)
     lg = O.scores(ref["q_tilde"], U.f32np(kd))
     gm, _ = _select_case(g, wl, [itd], ref["q_tilde"][None], 0.7)
-    assert U.check_rowmask_sandwich(gm, lg, U.p32(0.7), 1e-5) <= 2
+    assert U.check_rowmask_strict(gm, lg, U.p32(0.7), 1e-5) <= 2
     # one dominant key -> a single selected key per row
     kh = it["k"].clone() * 0.01
     kh[100] = 50.0 * torch.tensor(ref["q_tilde"][0].reshape(wl.n_kv_heads, wl.group, wl.d_k)[:, 0], dtype=torch.float32)
@@ -245,7 +248,10 @@ def test_select_bf16_fallbacks_and_ties(g):
     # the cut lies far below the maximum (p -> 1): beyond the histogram window
     for p in (0.999999, 0.9999999):
         gm, _ = _select_case(g, wl, [it], q, p)
-        nb = U.check_rowmask_sandwich(gm, ref["logits"], U.p32(p), min(stol, (1 - U.p32(p)) / 4))
+        # (p within 1e-6 of 1: fp32 weights cannot honour a band of (1 - p) / 4 on the mass itself, so the
+        # validity asserts use 1e-6; the interval band stays at (1 - p) / 4)
+        nb = U.check_rowmask_sandwich(gm, ref["logits"], U.p32(p), min(stol, (1 - U.p32(p)) / 4),
+                                      vtol=max((1 - U.p32(p)) / 2, 1e-6))
         say("  p", p, "boundary", nb, "mean row size", gm.sum(-1).mean())
     # all keys equal: every key lands in one bin, candidate lists overflow; ties -> lowest positions
     it0 = dict(it, k=torch.zeros_like(it["k"]))
@@ -258,13 +264,13 @@ def test_select_bf16_fallbacks_and_ties(g):
     lg = O.scores(ref["q_tilde"], U.f32np(kd))
     for p in (0.5, 0.95):
         gm, _ = _select_case(g, wl, [dict(it, k=kd)], q, p)
-        assert U.check_rowmask_sandwich(gm, lg, U.p32(p), stol) <= 8
+        assert U.check_rowmask_strict(gm, lg, U.p32(p), stol) <= 8
     # flatter attention: hundreds of keys share the cut bin (the larger candidate paths of the resolver)
     for scale in (0.25, 0.05):
         ks = (it["k"].to(torch.float32) * scale).to(it["k"].dtype)
         lg = O.scores(ref["q_tilde"], U.f32np(ks))
         gm, _ = _select_case(g, wl, [dict(it, k=ks)], q, 0.9)
-        nb = U.check_rowmask_sandwich(gm, lg, U.p32(0.9), stol)
+        nb = U.check_rowmask_strict(gm, lg, U.p32(0.9), stol)
         say("  key scale", scale, "boundary", nb, "mean row size", gm.sum(-1).mean())
     # a tiny p: only the arg-max key of each row
     gm, _ = _select_case(g, wl, [it], q, 1e-6)
@@ -398,6 +404,7 @@ def test_end_to_end_path(g, name):
         m = r["logits"].max(-1).reshape(-1)
         assert np.all(np.abs(pipe.row_max[i].cpu().numpy() - m) <= tol * (1 + np.abs(m)))
         say(f"  item {i}: L={L} budget gpu {budget[i].tolist()} oracle {r['budget'].tolist()}")
+        U.check_budgets(budget[i], r["budget"])
     say("  boundary keys", boundary)
 
 
@@ -434,7 +441,7 @@ def test_short_contexts_take_the_general_path(g):
         L = it["L"]
         gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
         off += pipe.mask_words[i]
-        U.check_rowmask_sandwich(gm, r["logits"], U.p32(wl.p), U.STAGE_TOL[wl.dtype])
+        U.check_rowmask_strict(gm, r["logits"], U.p32(wl.p), U.STAGE_TOL[wl.dtype])
 
 
 def test_algorithm1_mode_real_query_budget_then_topk(g):
@@ -474,9 +481,8 @@ def test_algorithm1_mode_real_query_budget_then_topk(g):
         lg0 = O.scores(q0[i], U.f32np(it["k"]))[0]                      # [H_q, L]
         m0 = U.unpack_rows(mask0[off0:off0 + hq * words[i]], hq, L)
         off0 += hq * words[i]
+        U.check_rowmask_strict(m0[None], lg0[None], p, U.STAGE_TOL["bf16"])     # the real query is the oracle's
         for h in range(hq):
-            must, may = U.band_sets(lg0[h], p, U.STAGE_TOL["bf16"])
-            assert not (must & ~m0[h]).any() and not (m0[h] & ~may).any()
             assert np.all(counts_h[i, :, h] == m0[h].sum())
         gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(S, hq, L)
         off += pipe.mask_words[i]
@@ -515,6 +521,7 @@ def test_more_items_than_one_launch_table_bf16(g):
         um = U.unpack_rows(pipe.union_mask[uoff[i]:uoff[i + 1]], wl.n_kv_heads, L)
         gu, gb = O.union_vote(gm, wl.n_kv_heads)
         assert np.array_equal(um, gu) and np.array_equal(budget[i], gb)
+        U.check_budgets(budget[i], r["budget"])
         ko, vo, idx, _ = O.compact(U.f32np(it["k"]), U.f32np(it["v"]), um)
         lo, hi = offsets[i * wl.n_kv_heads], offsets[(i + 1) * wl.n_kv_heads]
         assert np.array_equal(U.f32np(pipe.k_out[lo:hi]), ko) and np.array_equal(pipe.idx_out[lo:hi].cpu().numpy(), idx)

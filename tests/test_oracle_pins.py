@@ -414,6 +414,46 @@ def test_band_sets_bracket_the_oracle_selection():
         assert (may0 & ~must0).sum() <= 1 and np.all(sel[must0]) and np.all(may0[sel])
 
 
+def test_mask_checks_reject_planted_mistakes():
+    """The mask checks of the GPU parity tests, exercised on mistakes planted into the ORACLE's own
+    selection (CPU only): a set short of p by a whole heavy key (which the interval band alone lets pass),
+    a set with a superfluous key, a set that skips a heavier key for a lighter one."""
+    import sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    import parity_util as U
+    p, tol = 0.95, 2e-3
+    w = np.array([0.50, 0.44, 0.02, 0.015, 0.010] + [0.015 / 30] * 30)       # masses; cumulative 0.5, 0.94, 0.96 ...
+    l = np.log(w)
+    good = O.top_p_select(l, p)
+    assert good.sum() == 3
+    lg, gm = l[None, None, :], good[None, None, :]
+    assert U.check_rowmask_strict(gm, lg, p, tol) == 0 and U.check_rowmask_sandwich(gm, lg, p, tol) == 0
+    short = good.copy(); short[2] = False                 # mass 0.94: short of p - tol by the key that straddles p
+    must, may = U.band_sets(l, p, tol)
+    assert np.all(short[must]) and np.all(may[short])     # the band alone accepts it ...
+    for check in (U.check_rowmask_strict, U.check_rowmask_sandwich):
+        with pytest.raises(AssertionError):               # ... the validity asserts do not
+            check(short[None, None, :], lg, p, tol)
+    fat = good.copy(); fat[3] = True                       # one key too many: not minimal
+    skip = good.copy(); skip[2] = False; skip[3] = True; skip[4] = True        # lighter keys instead of a heavier one
+    for bad in (fat, skip):
+        for check in (U.check_rowmask_strict, U.check_rowmask_sandwich):
+            with pytest.raises(AssertionError):
+                check(bad[None, None, :], lg, p, tol)
+    # two nearly tied heavy keys at the boundary may swap end to end (band + validity) but not under the strict check
+    w2 = np.array([0.60, 0.30, 0.04, 0.0101, 0.0100] + [0.0399 / 40] * 40)   # cumulative 0.6, 0.9, 0.94, 0.9501
+    l2 = np.log(w2)
+    sel = O.top_p_select(l2, p)
+    assert sel.sum() == 4
+    swapped = sel.copy(); swapped[3] = False; swapped[4] = True              # mass 0.95 exactly, still reaches p - tol
+    U.check_rowmask_sandwich(swapped[None, None, :], l2[None, None, :], p, tol)
+    with pytest.raises(AssertionError):
+        U.check_rowmask_strict(swapped[None, None, :], l2[None, None, :], p, tol)
+    U.check_budgets([100, 4000], [104, 4080])
+    with pytest.raises(AssertionError):
+        U.check_budgets([100], [120])
+
+
 def test_workload_generator_is_seeded_and_shaped():
     from synth import workloads as W
     wl = W.scaled(W.config(5), lengths=(200, 90))
