@@ -144,9 +144,12 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
  * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
  * ws is required (gvote_workspace_bytes): statistics between the passes and the exact selector's logit cache.
- * Diagnostic: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
- * of ws holds, after the call and until ws is used again, the number of rows that had to be redone by the exact general selector
- * (cut outside the histogram window, or too many keys tied around the cut). */
+ * Diagnostics: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
+ * words of ws hold, after the call and until ws is used again: [0] the number of rows that had to be redone by
+ * the exact general selector, and [2..5] that number by reason: the cut lies below the histogram window; a
+ * row's candidate lists are full; more candidates around the cut than the resolver holds; a first-pass
+ * workgroup gave up waiting for one of its waves (see gvote_debug_set_spin_limit) - such rows are never
+ * answered from a partial histogram. */
 GVOTE_API gvote_status gvote_score_select(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
                                 int32_t S, const void *q, float p, int32_t mode, const int32_t *k_per_row,
                                 uint32_t *rowmask, float *row_max, float *row_sum,
@@ -195,6 +198,13 @@ GVOTE_API gvote_status gvote_decode_attention(const gvote_shape *shape, int32_t 
 GVOTE_API gvote_status gvote_attention_overlap(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
                                                int32_t S, const void *q_real, const uint32_t *rowmask,
                                                float *overlap, void *ws, size_t ws_bytes, void *stream);
+
+/* Test aid for the failure handling of gvote_score_select's first pass: a wave that has finished its keys
+ * polls for the other waves of its workgroup at most `polls` times before it gives up and the workgroup's
+ * rows go to the exact selector (default 1 << 22, never reached in normal operation; 0 makes nearly every
+ * workgroup give up, so the error path can be tested while every kernel still exits normally).  Process-wide,
+ * applies to later calls; a negative value restores the default.  Returns the previous limit. */
+GVOTE_API int32_t gvote_debug_set_spin_limit(int32_t polls);
 
 /* Test aid: out[e] (device uint32, e < n) = Philox4x32-10 draw e of stream (seed, stream_id),
  * the integer stream gvote_sample_queries consumes. */

@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
     L.gvote_decode_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.gvote_attention_overlap.restype = C.c_int
     L.gvote_attention_overlap.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.gvote_debug_set_spin_limit.restype = i32
+    L.gvote_debug_set_spin_limit.argtypes = [i32]
     L.gvote_philox_u32.restype = C.c_int
     L.gvote_philox_u32.argtypes = [u64, u64, i64, vp, vp]
     _lib = L
@@ -199,6 +201,10 @@ def attention_overlap(b: Batch, S: int, q_real: torch.Tensor, rowmask: torch.Ten
            "gvote_attention_overlap")
 
 
+def debug_set_spin_limit(polls: int) -> int:
+    return int(lib().gvote_debug_set_spin_limit(int(polls)))
+
+
 def philox_u32(seed: int, stream_id: int, n: int, out: torch.Tensor, stream=None) -> None:
     _check(lib().gvote_philox_u32(int(seed), int(stream_id), int(n), _ptr(out), _stream(stream)), "gvote_philox_u32")
 
@@ -250,8 +256,8 @@ class Pipeline:
         return int(self.ws[:4].view(torch.int32).item())
 
     def fallback_reasons(self):
-        """(cut below the histogram window, candidate sub-list overflow, too many candidates) row counts."""
-        return [int(x) for x in self.ws[8:20].view(torch.int32).tolist()]
+        """(cut below the histogram window, candidate lists full, too many candidates, first pass gave up) row counts."""
+        return [int(x) for x in self.ws[8:24].view(torch.int32).tolist()]
 
     def compact(self):
         union_compact(self.b, self.S, self.rowmask, self.union_mask, self.budget, self.offsets, self.k_out,

@@ -118,7 +118,15 @@ FitPlan plan_fit(const gvote_shape *sh, const gvote_item *items, int n_items) {
   FitPlan p;
   p.rows_per_chunk = (int)rpc;
   p.total_chunks = 0;
-  for (int i = 0; i < n_items; ++i) p.total_chunks += ceil_div(items[i].L - items[i].n_skip, rpc);
+  p.max_batch_chunks = 0;
+  long long in_batch = 0;
+  for (int i = 0; i < n_items; ++i) {
+    if (i % kMaxItems == 0) in_batch = 0;
+    const int c = ceil_div(items[i].L - items[i].n_skip, rpc);
+    p.total_chunks += c;
+    in_batch += c;
+    if (in_batch > p.max_batch_chunks) p.max_batch_chunks = in_batch;
+  }
   p.ws_bytes = (size_t)p.total_chunks * 2 * sh->d_model * sizeof(float);
   return p;
 }
@@ -149,7 +157,7 @@ gvote_status launch_fit(const gvote_shape *sh, const gvote_item *items, int n_it
       f.n_chunks = ceil_div(g.L - g.n_skip, plan.rows_per_chunk);
       c += f.n_chunks;
     }
-    if (c > 65535) return GVOTE_ERR_CAPACITY;
+    if (c > kMaxFitChunks) return GVOTE_ERR_CAPACITY;   // (the entry point has already checked the plan)
     const dim3 grid(colblocks, c);
     if (sh->dtype == GVOTE_F32)
       hipLaunchKernelGGL(moments_partial_kernel<float>, grid, dim3(kFitThreads), 0, st, tab);

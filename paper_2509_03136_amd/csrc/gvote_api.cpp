@@ -91,7 +91,9 @@ gvote_status gvote_fit_gaussian(const gvote_shape *shape, const gvote_item *item
   if ((st = check_items(shape, items, n_items, NEED_HIDDEN)) != GVOTE_OK) return st;
   if (!mu || !var || !ws || (ddof != 0 && ddof != 1)) return GVOTE_ERR_INVALID_ARG;
   if (!aligned16(mu) || !aligned16(var) || !aligned16(ws)) return GVOTE_ERR_SHAPE;
-  if (ws_bytes < plan_fit(shape, items, n_items).ws_bytes) return GVOTE_ERR_WORKSPACE;
+  const FitPlan fp = plan_fit(shape, items, n_items);
+  if (fp.max_batch_chunks > kMaxFitChunks) return GVOTE_ERR_CAPACITY;    // > 2.6e8 tokens in 32 items
+  if (ws_bytes < fp.ws_bytes) return GVOTE_ERR_WORKSPACE;
   return launch_fit(shape, items, n_items, ddof, mu, var, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
@@ -186,6 +188,8 @@ gvote_status gvote_attention_overlap(const gvote_shape *shape, const gvote_item 
   return launch_attention_overlap(shape, items, n_items, S, q_real, rowmask, overlap, ws,
                                   reinterpret_cast<hipStream_t>(stream));
 }
+
+int32_t gvote_debug_set_spin_limit(int32_t polls) { return set_hist_spin_limit(polls); }
 
 gvote_status gvote_philox_u32(uint64_t seed, uint64_t stream_id, int64_t n, uint32_t *out, void *stream) {
   if (n < 0 || (n > 0 && !out)) return GVOTE_ERR_INVALID_ARG;

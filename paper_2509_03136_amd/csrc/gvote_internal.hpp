@@ -12,6 +12,8 @@
 
 namespace gvote {
 
+constexpr size_t kLdsBytesPerCu = 160 * 1024;   // LDS of one gfx950 compute unit
+
 // Items per launch batch.  Tables are kernel arguments (<= 4 KiB), larger calls are split.
 constexpr int kMaxItems = 32;
 
@@ -147,9 +149,11 @@ struct FitTable {
   float *partial;       // [total_chunks][2][d]: chunk mean, chunk M2
   FitItem it[kMaxItems];
 };
+constexpr int kMaxFitChunks = 65535;   // row chunks of one launch batch (grid dimension y)
 struct FitPlan {
   int rows_per_chunk;
-  int total_chunks;     // over the whole call
+  int total_chunks;            // over the whole call
+  long long max_batch_chunks;  // most row chunks of any launch batch of the call
   size_t ws_bytes;
 };
 FitPlan plan_fit(const gvote_shape *sh, const gvote_item *items, int n_items);
@@ -222,7 +226,7 @@ constexpr int kOvfCap = 256;          // entries of a row's shared overflow list
 struct RowInfo {
   float mdot;       // row maximum of the raw dot product
   int astar;        // absolute bin index floor(dot * c1) in which the cut falls
-  int flag;         // 1: redo this row with the general selector
+  int flag;         // odd: redo this row with the general selector (1 window, 3 lists full, 5 too many candidates, 7 pass 1 gave up); 2: second resolve tier
   int pad;
   double above;     // weight of all keys in bins above astar (relative to exp(-max))
   double target;    // p * Z
@@ -243,7 +247,8 @@ struct FastTable {
   int item0, rows_per_item;
   int n_slots;              // (item, KV head, chunk) slots of the batch
   int emit_split, pad4;     // pass 2 cuts every chunk into this many pieces of at most 8192 keys (its LDS mask buffer)
-  int sub_per_row, pad0;    // candidate sub-lists per row = 16 * (most key chunks of an item in the batch)
+  int sub_per_row;          // candidate sub-lists per row = 16 * (most key chunks of an item in the batch)
+  int spin_limit;           // polls a finished pass-1 wave waits for the others before it gives up
   float scale, c1, c2, p;   // c1 = bins per raw-dot unit, c2 = log2(e) / sqrt(d_k)
   const void *q;
   uint32_t *rowmask;
@@ -264,6 +269,7 @@ struct FastTable {
 };
 struct FastPlan { size_t off_max, off_top, off_hist, off_info, off_cnt, off_cands, off_tmax, off_list, off_ovfc, off_ovf, ws_bytes; };
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
+int set_hist_spin_limit(int polls);   // returns the previous limit; negative restores the default
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
                                float p, uint32_t *rowmask, float *row_max, float *row_sum, void *ws, hipStream_t st);

@@ -297,8 +297,11 @@ SamplePlan plan_sample(const gvote_shape *sh, int n_items, int S) {
   p.SP = (S + 31) / 32 * 32;
   p.SPs = (S + 7) / 8 * 8;
   if (use_mfma(sh, S)) {
-    // k-slices of 512 channels (a multiple of the 64-channel MFMA step); the last may be shorter
-    p.kslice = sh->d_model < 512 ? (sh->d_model + 63) / 64 * 64 : 512;
+    // k-slices of 512 channels (a multiple of the 64-channel MFMA step); the last may be shorter.  With
+    // 97..128 samples the staged sample block of a 512-channel slice (128 x 520 x 2 B) plus the wave tiles
+    // would not fit the 160 KiB of LDS: those calls use 256-channel slices (100 KiB).
+    const int full = p.SP > 96 ? 256 : 512;
+    p.kslice = sh->d_model < full ? (sh->d_model + 63) / 64 * 64 : full;
     p.ksplits = (sh->d_model + p.kslice - 1) / p.kslice;
   } else {
     p.kslice = sh->d_model;
@@ -346,12 +349,18 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
       const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, nb);
       const int nsb = plan.SP / 32;
       const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
+      if (lds > kLdsBytesPerCu) return GVOTE_ERR_CAPACITY;       // cannot happen with the slices plan_sample picks
+      hipError_t attr = hipSuccess;                               // more than 64 KiB of dynamic LDS must be asked for
+      if (nsb == 2 && lds > 65536)
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<2>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 3)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 4)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (attr != hipSuccess) return GVOTE_ERR_HIP;
       if (nsb == 1)
         hipLaunchKernelGGL(project_mfma_kernel<1>, gp, dim3(kProjWaves * 64), lds, st, tab);
       else if (nsb == 2)

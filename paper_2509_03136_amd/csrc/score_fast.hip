@@ -217,10 +217,11 @@ struct HistCtl {
   int pending, done, aborted, pad;
 };
 constexpr int kTopUnset = -(1 << 24);
+constexpr int kTopGaveUp = -(1 << 25);   // part_top of a (slot, row) whose pass-1 workgroup gave up: find_bin sends the row to the exact selector
 constexpr int kHeadroom = 4 * kBinsPerUnit;
 
 template <int DK, bool TWO>
-__device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
+__device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
                                                 unsigned char *ldstile, uint32_t *hist, HistCtl *S) {
   constexpr int LOADS = Tile<DK>::LOADS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
@@ -279,7 +280,8 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
         if (lane == 0) S->top[row] = newtop;
       }
     }
-    if (tid == 0) *pending = 0;       // between the barriers: nobody can be asking right now
+    if (lane == 0) *pending = 0;      // between the barriers: nobody can be asking right now (every wave writes it:
+                                      // no single wave's presence is needed, a wave may have given up and left)
     __syncthreads();
     top[0] = S->top[col];
     top[1] = S->top[32 + col];
@@ -377,16 +379,19 @@ __device__ __forceinline__ bool hist_fused_body(const FastTable &tab, const WgCo
   for (int spins = 0;; ++spins) {
     if (__builtin_amdgcn_readfirstlane(*pending) != 0) {
       sync_event();
-      continue;
+    } else if (__builtin_amdgcn_readfirstlane(*done) >= kWaves) {
+      break;
     }
-    if (__builtin_amdgcn_readfirstlane(*done) >= kWaves) break;
-    if (spins > (1 << 22)) {          // never reached if the protocol holds; a stuck wave must not hang the GPU
-      S->aborted = 1;
-      return false;
+    if (spins >= tab.spin_limit) {    // never reached if the protocol holds; a stuck wave must not hang the GPU.
+      // Give up VISIBLY: the flag is read by every wave after the workgroup's closing barrier (which this
+      // wave now joins; waves still inside an event pair up with it and finish on their own, because ended
+      // waves no longer count at a barrier), the workgroup then publishes kTopGaveUp for all its rows and
+      // find_bin hands those rows to the exact selector.  Events count as polls, so the loop is bounded.
+      if (lane == 0) *(volatile int *)&S->aborted = 1;
+      break;
     }
     __builtin_amdgcn_s_sleep(1);
   }
-  return true;
 }
 
 template <int DK>
@@ -407,18 +412,18 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
   }
   if (tid == 0) { ctl.pending = 0; ctl.done = 0; ctl.aborted = 0; }
   __syncthreads();
-  bool ok;
   if (c.n0 + 32 < tab.NQ)
-    ok = hist_fused_body<DK, true>(tab, c, I, tiles[wave], hist, &ctl);
+    hist_fused_body<DK, true>(tab, c, I, tiles[wave], hist, &ctl);
   else
-    ok = hist_fused_body<DK, false>(tab, c, I, tiles[wave], hist, &ctl);
-  if (!ok) return;
+    hist_fused_body<DK, false>(tab, c, I, tiles[wave], hist, &ctl);
   __syncthreads();
   const int rows = min(64, tab.NQ - c.n0);
+  const bool gave_up = *(volatile int *)&ctl.aborted != 0;
   if (tid < rows) {
     tab.part_max[(size_t)c.slot * tab.NQ + c.n0 + tid] = from_ordered_bits(ctl.rowmax[tid]);
-    tab.part_top[(size_t)c.slot * tab.NQ + c.n0 + tid] = ctl.top[tid];
+    tab.part_top[(size_t)c.slot * tab.NQ + c.n0 + tid] = gave_up ? kTopGaveUp : ctl.top[tid];
   }
+  if (gave_up) return;            // (wave-uniform: read after the barrier)
   uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
   for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
 }
@@ -437,9 +442,23 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
   float m = -INFINITY;
   int top = kTopUnset;
+  bool gave_up = false;
   for (int ch = 0; ch < I.n_chunks; ++ch) {
     m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
-    top = max(top, tab.part_top[(slot0 + ch) * tab.NQ + n]);
+    const int tc = tab.part_top[(slot0 + ch) * tab.NQ + n];
+    gave_up = gave_up || tc == kTopGaveUp;
+    top = max(top, tc);
+  }
+  RowInfo *info = tab.info + grow;
+  if (gave_up) {      // a pass-1 workgroup of this row gave up: no histogram to trust, the exact selector redoes the row
+    if (lane == 0) {
+      info->mdot = m;
+      info->astar = 0x7FFFFFFF;   // pass 2 ignores the row
+      info->flag = 7;
+      info->above = 0.0;
+      info->target = 0.0;
+      tab.ovf_cnt[grow] = 0;
+    }
   }
   // Every chunk binned inside its own window; on the absolute grid its bin jl is global bin
   // jl + (top - top_chunk).  Weights are fixed-point sums relative to the bin's upper edge, so the
@@ -489,12 +508,11 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   }
   const double Z = base;
   const double target = (double)tab.p * Z;
-  RowInfo *info = tab.info + grow;
 #pragma unroll
   for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
     const double before = cum[i] - mine[i];
-    if (before < target && cum[i] >= target) {
+    if (!gave_up && before < target && cum[i] >= target) {
       info->mdot = m;
       info->astar = top - j;
       info->flag = (j == kBins - 1) ? 1 : 0;      // 1: the cut lies below the histogram window
@@ -507,7 +525,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     if (grow == 0) {
       if (tab.item0 == 0) {
         *tab.n_fallback = 0;
-        tab.n_list[1] = 0; tab.n_list[2] = 0; tab.n_list[3] = 0;
+        tab.n_list[1] = 0; tab.n_list[2] = 0; tab.n_list[3] = 0; tab.n_list[4] = 0;
       }
       *tab.n_list = 0;
     }
@@ -745,7 +763,7 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   if (SECOND && (flag & 1)) {           // settled as "needs the exact selector": queue the row
     if (lane == 0) {
       tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
-      atomicAdd(tab.n_list + 1 + (flag >> 1), 1);      // diagnostic: rows by reason (window, sub-list, capacity)
+      atomicAdd(tab.n_list + 1 + (flag >> 1), 1);      // diagnostic: rows by reason (window, sub-list, capacity, gave up)
     }
     return;
   }
@@ -866,7 +884,15 @@ int pick_chunk_keys(const gvote_shape *sh, const gvote_item *items, int n_items)
 }
 int emit_split_of(int chunk_keys) { return chunk_keys > kMaxEmitKeys ? 2 : 1; }
 
+int g_spin_limit = 1 << 22;     // polls of a finished pass-1 wave waiting for its workgroup before it gives up
+
 }  // namespace
+
+int set_hist_spin_limit(int polls) {
+  const int old = g_spin_limit;
+  g_spin_limit = polls < 0 ? (1 << 22) : polls;
+  return old;
+}
 
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p) {
   const int NQ = S * (sh->n_q_heads / sh->n_kv_heads);
@@ -925,6 +951,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.c1 = tab.scale * (float)kBinsPerUnit;
     tab.c2 = tab.scale * 1.44269504088896340736f;
     tab.p = p;
+    tab.spin_limit = g_spin_limit;
     tab.q = q; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.n_list = reinterpret_cast<int *>(wsb) + 1;
@@ -954,7 +981,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       mask_off += (long long)tab.rows_per_item * f.W;
     }
     tab.emit_split = emit_split_of(tab.chunk_keys); tab.pad4 = 0;
-    tab.sub_per_row = most_chunks * tab.emit_split * 2 * kWaves; tab.pad0 = 0;
+    tab.sub_per_row = most_chunks * tab.emit_split * 2 * kWaves;
     tab.n_slots = part;
     const int grid_wg = tab.NQB == 1 ? wg : ceil_div(part, 8) * 8 * tab.NQB;
     const int rows = nb * tab.rows_per_item;

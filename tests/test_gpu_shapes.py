@@ -1,0 +1,134 @@
+"""GPU parity on the kernel instantiations that the five benchmark shapes do not reach: head_dim 64 on the
+bf16 matrix-core score path, 33..128 samples (the wider projection tiles, several 64-row blocks per KV
+group), a hidden size that is not a multiple of the projection's k-slice, more than eight query heads per
+KV head on the consumer side, and the failure handling of the first score pass (forced from the host
+through the spin-limit test aid; every kernel still exits normally)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import parity_util as U
+from synth import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2509_03136_amd as g
+    g.lib()
+    assert torch.cuda.is_available()
+    return g
+
+
+def _stage_by_stage(g, wl):
+    """sample (given the oracle's moments) and select (given the oracle's queries) against the oracle."""
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it) for it in items]
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, wl.p)
+    pipe.mu.copy_(torch.tensor(np.stack([r["mu"] for r in refs])))
+    pipe.var.copy_(torch.tensor(np.stack([r["var"] for r in refs])))
+    pipe.sample()
+    torch.cuda.synchronize()
+    for i, r in enumerate(refs):
+        q = U.f32np(pipe.q[i]).astype(np.float64)
+        qd = np.abs(q - r["q_tilde"])
+        scale = np.sqrt((r["q_tilde"] ** 2).mean())
+        assert np.all(qd <= 2.0 ** -7 * np.abs(r["q_tilde"]) + U.TOL[wl.dtype] * scale), qd.max()
+        assert (qd > 0).mean() < 0.05, (qd > 0).mean()
+    pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+    pipe.select()
+    torch.cuda.synchronize()
+    n_fb = pipe.fallback_rows()
+    off = boundary = 0
+    for i, (it, r) in enumerate(zip(items, refs)):
+        L = it["L"]
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
+        off += pipe.mask_words[i]
+        boundary += U.check_rowmask_strict(gm, r["logits"], U.p32(wl.p), U.STAGE_TOL[wl.dtype])
+        m = r["logits"].max(-1).reshape(-1)
+        assert np.all(np.abs(pipe.row_max[i].cpu().numpy() - m) <= U.STAGE_TOL[wl.dtype] * (1 + np.abs(m)))
+    pipe.compact()
+    torch.cuda.synchronize()
+    budget = pipe.budget.cpu().numpy()
+    for i, r in enumerate(refs):
+        U.check_budgets(budget[i], r["budget"], slack_keys=2 + boundary, rel=0.0)
+    return boundary, n_fb
+
+
+@pytest.mark.parametrize("S", [48, 96, 128])
+def test_wide_sample_blocks_and_odd_hidden_size(g, S):
+    # d = 832 = 512 + 320: the projection's last k-slice is short (and for S > 96 the slices are 256 wide);
+    # S * G = 96 .. 256 query rows per KV head: two to four 64-row blocks in the score passes
+    wl = W.scaled(W.config(2), lengths=(1500, 333), n_planted=(20, 4), d=832, n_q_heads=4, n_kv_heads=2, S=S)
+    boundary, n_fb = _stage_by_stage(g, wl)
+    say(f"  S={S}: boundary keys {boundary}, fallback rows {n_fb}")
+    assert boundary <= 8
+
+
+def test_head_dim_64_on_the_matrix_core_path(g):
+    wl = W.scaled(W.config(2), lengths=(2100, 77), n_planted=(30, 2), d=1024, n_q_heads=16, n_kv_heads=4, d_k=64, S=16)
+    boundary, n_fb = _stage_by_stage(g, wl)
+    say(f"  head_dim 64: boundary keys {boundary}, fallback rows {n_fb}")
+    assert boundary <= 8
+
+
+def test_decode_attention_sixteen_heads_per_kv_head(g):
+    wl = W.scaled(W.config(2), lengths=(900, 130), n_planted=(10, 2), d=1024, n_q_heads=32, n_kv_heads=2, d_k=64, S=4)
+    items = W.make_items(wl, "cpu")
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, wl.p, ddof=wl.ddof)
+    pipe.run()
+    gen = torch.Generator().manual_seed(11)
+    q = torch.randn(len(items), wl.n_q_heads, wl.d_k, generator=gen).to(torch.bfloat16)
+    q_dev = q.to(DEV)
+    out = torch.empty_like(q_dev)
+    lse = torch.empty(len(items), wl.n_q_heads, device=DEV, dtype=torch.float32)
+    g.decode_attention(b, q_dev, pipe.k_out, pipe.v_out, pipe.offsets, out, lse)
+    torch.cuda.synchronize()
+    offs = pipe.offsets.cpu().numpy()
+    k_out, v_out = U.f32np(pipe.k_out), U.f32np(pipe.v_out)
+    for i in range(len(items)):
+        o = offs[i * wl.n_kv_heads:(i + 1) * wl.n_kv_heads + 1]
+        want, want_lse = O.decode_attention(U.f32np(q[i]), k_out, v_out, o, wl.n_kv_heads)
+        got = U.f32np(out[i]).astype(np.float64)
+        scale = np.sqrt((want ** 2).mean())
+        assert np.all(np.abs(got - want) <= 2.0 ** -7 * np.abs(want) + 2e-3 * scale + 1e-6), np.abs(got - want).max()
+        assert np.all(np.abs(lse[i].cpu().numpy() - want_lse) <= 2e-3 * (1 + np.abs(want_lse)))
+
+
+def test_first_pass_give_up_path_sends_rows_to_the_exact_selector(g):
+    """With a spin limit of 0 a first-pass wave that finishes before its workgroup gives up at once: the
+    workgroup publishes no histogram, its rows are flagged and the exact selector redoes them.  The masks
+    must still be the oracle's, and the give-up counter must say what happened."""
+    wl = W.scaled(W.config(2), lengths=(3000, 1100), n_planted=(40, 10), S=8)
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it) for it in items]
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, wl.p)
+    pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+    old = g.debug_set_spin_limit(0)
+    try:
+        pipe.select()
+        torch.cuda.synchronize()
+    finally:
+        g.debug_set_spin_limit(old)
+    n_fb, why = pipe.fallback_rows(), pipe.fallback_reasons()
+    say(f"  spin limit 0: {n_fb} rows redone exactly, by reason {why}")
+    assert why[3] > 0 and n_fb >= why[3]
+    off = 0
+    for i, (it, r) in enumerate(zip(items, refs)):
+        L = it["L"]
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, L).reshape(wl.S, wl.n_q_heads, L)
+        off += pipe.mask_words[i]
+        U.check_rowmask_strict(gm, r["logits"], U.p32(wl.p), U.STAGE_TOL[wl.dtype])
+    pipe.select()                       # and with the default limit nothing gives up
+    torch.cuda.synchronize()
+    assert pipe.fallback_reasons()[3] == 0
