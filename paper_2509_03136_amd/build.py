@@ -12,6 +12,19 @@ LIB = os.path.join(HERE, "libgvote.so")
 SOURCES = ["gvote_api.cpp", "fit_gaussian.hip", "sample_queries.hip", "score_select.hip", "score_fast.hip", "union_compact.hip", "consumer.hip"]
 
 
+def sources_digest() -> str:
+    """sha256 over the library's sources (kernels, internal header, C ABI header): stamps profile
+    summaries so that a reader can tell which kernels a summary was taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    paths = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".hpp", ".cpp"))]
+    paths.append(os.path.join(ROOT, "include", "gvote.h"))
+    for path in paths:
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def build(verbose: bool = True, out: str = LIB, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden", "-x", "hip",
