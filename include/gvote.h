@@ -174,6 +174,22 @@ GVOTE_API gvote_status gvote_union_compact(const gvote_shape *shape, const gvote
                                  int64_t capacity_tokens, int32_t *overflow_flag,
                                  void *ws, size_t ws_bytes, void *stream);
 
+/* gvote_union_compact for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * gvote_union_compact without `ws`: the chunk counts, chunk bases and head indices of the call live in a
+ * fixed 1 MiB array inside the library's device image (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing.  Limit: 12 bytes per 2048-token chunk of a KV head plus 4 per
+ * (item, head) must fit the array (about 87 000 chunks, i.e. 1.7e8 head-tokens per call); larger calls
+ * return GVOTE_ERR_CAPACITY before any launch.  The calling thread's current device must be the stream's
+ * device; the array's address is looked up on the first call on each device.  All calls on one GPU share
+ * the array (every call rewrites all of it that it reads, nothing needs clearing): calls that overlap in
+ * time on one GPU race - issue them on one stream or order them. */
+GVOTE_API gvote_status gvote_union_compact_static(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
+                                 int32_t S, const uint32_t *rowmask,
+                                 uint32_t *union_mask, int32_t *budget, int64_t *offsets,
+                                 void *k_out, void *v_out, int32_t *idx_out,
+                                 int64_t capacity_tokens, int32_t *overflow_flag, void *stream);
+
 /* Alg. 1 "B_step <- |C_0|": sizes of row sets.  counts[i, c, r] (device int32, [n_items, repeat, S * n_q_heads])
  * = number of keys selected in row r of item i's row masks, written `repeat` times over.  With the masks
  * of the REAL current query (S = 1, GVOTE_SELECT_TOPP) and repeat = number of synthetic samples, the

@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
     L.gvote_score_select.argtypes = [sp, ip, i32, i32, vp, f32, i32, vp, vp, vp, vp, vp, sz, vp]
     L.gvote_union_compact.restype = C.c_int
     L.gvote_union_compact.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.gvote_union_compact_static.restype = C.c_int
+    L.gvote_union_compact_static.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, vp]
     L.gvote_count_rows.restype = C.c_int
     L.gvote_count_rows.argtypes = [sp, ip, i32, i32, vp, i32, vp, vp]
     L.gvote_decode_attention.restype = C.c_int
@@ -181,6 +183,16 @@ def union_compact(b: Batch, S: int, rowmask: torch.Tensor, union_mask: torch.Ten
                                      _ptr(budget), _ptr(offsets), _ptr(k_out), _ptr(v_out), _ptr(idx_out),
                                      int(capacity_tokens), _ptr(overflow_flag), _ptr(ws),
                                      ws.numel() * ws.element_size(), _stream(stream)), "gvote_union_compact")
+
+
+def union_compact_static(b: Batch, S: int, rowmask: torch.Tensor, union_mask: torch.Tensor, budget: torch.Tensor,
+                         offsets: torch.Tensor, k_out: torch.Tensor, v_out: torch.Tensor,
+                         idx_out: Optional[torch.Tensor], capacity_tokens: int, overflow_flag: torch.Tensor,
+                         stream=None) -> None:
+    _check(lib().gvote_union_compact_static(C.byref(b.shape), b.items, b.n_items, S, _ptr(rowmask), _ptr(union_mask),
+                                            _ptr(budget), _ptr(offsets), _ptr(k_out), _ptr(v_out), _ptr(idx_out),
+                                            int(capacity_tokens), _ptr(overflow_flag), _stream(stream)),
+           "gvote_union_compact_static")
 
 
 def count_rows(b: Batch, S: int, rowmask: torch.Tensor, repeat: int, counts: torch.Tensor, stream=None) -> None:

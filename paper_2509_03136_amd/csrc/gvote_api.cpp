@@ -153,6 +153,26 @@ gvote_status gvote_union_compact(const gvote_shape *shape, const gvote_item *ite
                               overflow_flag, ws, reinterpret_cast<hipStream_t>(stream));
 }
 
+gvote_status gvote_union_compact_static(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
+                                        const uint32_t *rowmask, uint32_t *union_mask, int32_t *budget,
+                                        int64_t *offsets, void *k_out, void *v_out, int32_t *idx_out,
+                                        int64_t capacity_tokens, int32_t *overflow_flag, void *stream) {
+  gvote_status st = check_shape(shape);
+  if (st != GVOTE_OK) return st;
+  if ((st = check_items(shape, items, n_items, NEED_K | NEED_V)) != GVOTE_OK) return st;
+  if (!rowmask || !union_mask || !budget || !offsets || !k_out || !v_out || !overflow_flag || S < 1 ||
+      capacity_tokens < 0)
+    return GVOTE_ERR_INVALID_ARG;
+  if (S > 128) return GVOTE_ERR_CAPACITY;
+  if (!aligned16(k_out) || !aligned16(v_out)) return GVOTE_ERR_SHAPE;
+  if (plan_union(shape, items, n_items).ws_bytes > kStaticScratchBytes) return GVOTE_ERR_CAPACITY;
+  void *scratch_ptr = nullptr;
+  if ((st = static_scratch_of_current_device(&scratch_ptr)) != GVOTE_OK) return st;
+  return launch_union_compact(shape, items, n_items, S, rowmask, union_mask, budget,
+                              reinterpret_cast<long long *>(offsets), k_out, v_out, idx_out, capacity_tokens,
+                              overflow_flag, scratch_ptr, reinterpret_cast<hipStream_t>(stream));
+}
+
 gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,
                               const uint32_t *rowmask, int32_t repeat, int32_t *counts, void *stream) {
   gvote_status st = check_shape(shape);

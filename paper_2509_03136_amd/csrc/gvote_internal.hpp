@@ -310,6 +310,9 @@ struct UnionTable {
 };
 struct UnionPlan { int total_chunks; size_t off_base, off_head, ws_bytes; };
 UnionPlan plan_union(const gvote_shape *sh, const gvote_item *items, int n_items);
+// the static scratch array of stage 4 (one per device): its size, and its address on the current device
+constexpr size_t kStaticScratchBytes = 1 << 20;
+gvote_status static_scratch_of_current_device(void **ptr);
 gvote_status launch_union_compact(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
                                   const uint32_t *rowmask, uint32_t *union_mask, int *budget, long long *offsets,
                                   void *k_out, void *v_out, int *idx_out, long long capacity, int *overflow_flag,

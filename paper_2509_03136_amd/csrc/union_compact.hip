@@ -10,11 +10,22 @@
 //                 positions in LDS, then copy the K and V rows with 16-byte lanes (a 256-byte row
 //                 is 16 lanes), rows in ascending position: a stable stream compaction.
 // Everything here is integer / byte work and bit-exact by construction.
+#include <mutex>
+
 #include "gvote_internal.hpp"
+
+// Scratch memory of the entry point that allocates nothing (gvote_union_compact_static): chunk counts,
+// chunk bases and first-chunk indices of one call.  One copy per GPU the library runs on, held until the
+// process ends; in host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[gvote::kStaticScratchBytes];
 
 namespace gvote {
 
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, looked up once
+std::mutex g_scratch_mutex;
 
 // grid: one wave per chunk, 4 chunks per workgroup
 __global__ __launch_bounds__(256) void union_count_kernel(const UnionTable tab) {
@@ -196,6 +207,20 @@ gvote_status launch_count_rows(const gvote_shape *sh, const gvote_item *items, i
     hipLaunchKernelGGL(count_rows_kernel, dim3(ceil_div(nb * tab.rows_per_item, 4)), dim3(256), 0, st, tab);
     GVOTE_CHECK_LAUNCH();
   }
+  return GVOTE_OK;
+}
+
+gvote_status static_scratch_of_current_device(void **ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return GVOTE_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return GVOTE_ERR_CAPACITY;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return GVOTE_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
   return GVOTE_OK;
 }
 
