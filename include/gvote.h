@@ -144,7 +144,7 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
  * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
  * ws is required (gvote_workspace_bytes): statistics between the passes and the exact selector's logit cache.
- * Diagnostics: when the matrix-core path runs (bf16, head_dim 64 or 128, TOPP, p < 1) the first int32
+ * Diagnostics: when the matrix-core path runs (bf16, head_dim 64 or 128, every L >= 32; TOPP with p < 1, or TOPK) the first int32
  * words of ws hold, after the call and until ws is used again: [0] the number of rows that had to be redone by
  * the exact general selector, and [2..5] that number by reason: the cut lies below the histogram window; a
  * row's candidate lists are full; more candidates around the cut than the resolver holds; a first-pass

@@ -228,8 +228,8 @@ struct RowInfo {
   int astar;        // absolute bin index floor(dot * c1) in which the cut falls
   int flag;         // odd: redo this row with the general selector (1 window, 3 lists full, 5 too many candidates, 7 pass 1 gave up); 2: second resolve tier
   int pad;
-  double above;     // weight of all keys in bins above astar (relative to exp(-max))
-  double target;    // p * Z
+  double above;     // weight of all keys in bins above astar (relative to exp(-max)); their number in TOPK mode
+  double target;    // p * Z; k in TOPK mode
 };
 struct FastItem {
   const void *k;
@@ -246,11 +246,13 @@ struct FastTable {
   int n_items, S, Hq, Hkv, G, NQ, NQB, chunk_keys;
   int item0, rows_per_item;
   int n_slots;              // (item, KV head, chunk) slots of the batch
-  int emit_split, pad4;     // pass 2 cuts every chunk into this many pieces of at most 8192 keys (its LDS mask buffer)
+  int emit_split;           // pass 2 cuts every chunk into this many pieces of at most 8192 keys (its LDS mask buffer)
+  int mode;                 // gvote_select_mode: TOPP bins softmax weights, TOPK bins key counts
   int sub_per_row;          // candidate sub-lists per row = 16 * (most key chunks of an item in the batch)
   int spin_limit;           // polls a finished pass-1 wave waits for the others before it gives up
   float scale, c1, c2, p;   // c1 = bins per raw-dot unit, c2 = log2(e) / sqrt(d_k)
   const void *q;
+  const int *k_per_row;     // TOPK: call-indexed row budgets
   uint32_t *rowmask;
   float *row_max, *row_sum;
   float *part_max;          // [slot][NQ]: chunk maximum of the raw dot
@@ -272,7 +274,8 @@ bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p);
 int set_hist_spin_limit(int polls);   // returns the previous limit; negative restores the default
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S);
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
-                               float p, uint32_t *rowmask, float *row_max, float *row_sum, void *ws, hipStream_t st);
+                               float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
+                               float *row_sum, void *ws, hipStream_t st);
 // the exact general selector on a batch of <= kMaxItems items; with `row_list` only the listed rows
 gvote_status launch_select_rows_general(const gvote_shape *sh, const gvote_item *items, int nb, int item0, int S,
                                         const void *q, float p, int mode, const int *k_per_row, uint32_t *rowmask,

@@ -1,5 +1,6 @@
 // Stage 3, bf16 fast path - K-streaming scores on the matrix cores and a histogram search for the
-// mass-p cut (paper Eq. (1) logits and softmax weights; Sec. 3.1 minimal key set of mass p).
+// mass-p cut (paper Eq. (1) logits and softmax weights; Sec. 3.1 minimal key set of mass p).  Alg. 1's
+// row-wise TopK on logits is the same search with unit weights (bins hold key counts, the target is k).
 //
 // Nothing of size S*H_q*L is stored: logits are recomputed from K in each pass, bit-identically
 // (same MFMA sequence), and only per-row statistics travel between the passes.
@@ -220,7 +221,7 @@ constexpr int kTopUnset = -(1 << 24);
 constexpr int kTopGaveUp = -(1 << 25);   // part_top of a (slot, row) whose pass-1 workgroup gave up: find_bin sends the row to the exact selector
 constexpr int kHeadroom = 4 * kBinsPerUnit;
 
-template <int DK, bool TWO>
+template <int DK, bool TWO, bool TOPK>
 __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
                                                 unsigned char *ldstile, uint32_t *hist, HistCtl *S) {
   constexpr int LOADS = Tile<DK>::LOADS;
@@ -258,7 +259,7 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
           v[i] = h[j];
           const long long jn = j + sh;
           if (jn >= kBins - 1 && v[i] != 0u)
-            spill += (float)v[i] * __builtin_amdgcn_exp2f(-(float)(jn - (kBins - 1)) * kLog2ePerBin);
+            spill += TOPK ? (float)v[i] : (float)v[i] * __builtin_amdgcn_exp2f(-(float)(jn - (kBins - 1)) * kLog2ePerBin);
         }
         for (int off = 32; off > 0; off >>= 1) spill += __shfl_xor(spill, off, 64);
         __builtin_amdgcn_wave_barrier();
@@ -341,8 +342,8 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
           for (int r = 0; r < 16; ++r) {
             const float d = acc[nb][r];
             const float af = fmaxf(floorf(d * c1), atail);
-            const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
-            const uint32_t u = (uint32_t)__builtin_amdgcn_exp2f(x);
+            uint32_t u = 1u;        // TOPK counts keys
+            if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
             lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
             if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bounds the scheduler's look-ahead (registers)
           }
@@ -358,8 +359,9 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
           for (int r = 0; r < 16; ++r) {
             const float d = acc[nb][r];
             const float af = fmaxf(floorf(d * c1), atail);
-            const float x = fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias));
-            const uint32_t u = key_of(r, hf) >= skip ? (uint32_t)__builtin_amdgcn_exp2f(x) : 0u;
+            uint32_t u = 1u;
+            if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
+            if (key_of(r, hf) < skip) u = 0u;
             lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
           }
         }
@@ -394,7 +396,7 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
   }
 }
 
-template <int DK>
+template <int DK, bool TOPK>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable tab) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ uint32_t hist[64 * (kBins + 1)];
@@ -413,9 +415,9 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
   if (tid == 0) { ctl.pending = 0; ctl.done = 0; ctl.aborted = 0; }
   __syncthreads();
   if (c.n0 + 32 < tab.NQ)
-    hist_fused_body<DK, true>(tab, c, I, tiles[wave], hist, &ctl);
+    hist_fused_body<DK, true, TOPK>(tab, c, I, tiles[wave], hist, &ctl);
   else
-    hist_fused_body<DK, false>(tab, c, I, tiles[wave], hist, &ctl);
+    hist_fused_body<DK, false, TOPK>(tab, c, I, tiles[wave], hist, &ctl);
   __syncthreads();
   const int rows = min(64, tab.NQ - c.n0);
   const bool gave_up = *(volatile int *)&ctl.aborted != 0;
@@ -465,6 +467,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   // chunks' sums of one absolute bin simply add: mass = sum * 2^-kFixBits * exp2(edge - max) in log2
   // units.  Chunk bins at or beyond the last global bin (and the chunks' own last bins) all fall into
   // the last global bin.  A lane owns bins lane, lane + 64, lane + 128, ...
+  const bool topk = tab.mode == GVOTE_SELECT_TOPK;
   const double mref = (double)m * (double)tab.c2;
   constexpr int BPL = kBins / 64;     // bins per lane
   unsigned long long acc[BPL];
@@ -480,7 +483,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
       const uint32_t u = hc[j];                       // chunk bin j
       const long long gbin = (long long)j + shift;     // where it lands globally
       if (gbin >= kBins - 1 && u)
-        tailpart += (float)u * __builtin_amdgcn_exp2f(-(float)(gbin - (kBins - 1)) * kLog2ePerBin);
+        tailpart += topk ? (float)u : (float)u * __builtin_amdgcn_exp2f(-(float)(gbin - (kBins - 1)) * kLog2ePerBin);
       const long long jl = (long long)j - shift;        // chunk bin that lands in my global bin j
       if (j < kBins - 1 && jl >= 0) acc[i] += hc[jl];
     }
@@ -490,9 +493,13 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
 #pragma unroll
   for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
-    mine[i] = acc[i] ? ldexp((double)acc[i], -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0;
-    if (j == kBins - 1)
-      mine[i] = ldexp((double)tailpart, -kFixBits) * exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
+    if (topk) {              // key counts
+      mine[i] = j == kBins - 1 ? (double)tailpart : (double)acc[i];
+    } else {
+      mine[i] = acc[i] ? ldexp((double)acc[i], -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0;
+      if (j == kBins - 1)
+        mine[i] = ldexp((double)tailpart, -kFixBits) * exp2((double)(top - (kBins - 1) + 1) * (double)kLog2ePerBin - mref);
+    }
   }
   // inclusive scan over bins (bin 0 = highest logits): within each group of 64 bins, then across groups
   double cum[BPL], base = 0.0;
@@ -507,7 +514,12 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     base += __shfl(x, 63, 64);
   }
   const double Z = base;
-  const double target = (double)tab.p * Z;
+  double target = (double)tab.p * Z;
+  if (topk) {
+    int k = tab.k_per_row[(size_t)(tab.item0 + it) * tab.rows_per_item + r];
+    k = k < 1 ? 1 : (k > I.L ? I.L : k);
+    target = (double)k;
+  }
 #pragma unroll
   for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
@@ -774,7 +786,8 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   // fixed-point scale: weights relative to the upper edge of the cut bin, 2^kFixBits each at most
   const double edge = (double)(info->astar + 1) * (double)kLog2ePerBin;       // log2 units
   const float efix = (float)((double)kFixBits - edge);
-  const double unit = exp2((double)info->mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);
+  const bool topk = tab.mode == GVOTE_SELECT_TOPK;
+  const double unit = topk ? 1.0 : exp2((double)info->mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);
   const double target = info->target * unit;
   double above = info->above * unit;
 
@@ -796,7 +809,7 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
         const uint2 e = src[i];
         const float d = __uint_as_float(e.x);
         M.key[dst0 + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-        M.wgt[dst0 + i] = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
+        M.wgt[dst0 + i] = topk ? 1u : (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
       }
     }
     cnt += __shfl(x, 63, 64);
@@ -808,7 +821,7 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
         const uint2 e = tab.ovf[(size_t)grow * kOvfCap + i];
         const float d = __uint_as_float(e.x);
         M.key[cnt + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-        M.wgt[cnt + i] = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
+        M.wgt[cnt + i] = topk ? 1u : (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
       }
     }
     cnt += n_ovf;
@@ -896,8 +909,8 @@ int set_hist_spin_limit(int polls) {
 
 bool fast_path_ok(const gvote_shape *sh, int S, int mode, float p) {
   const int NQ = S * (sh->n_q_heads / sh->n_kv_heads);
-  return sh->dtype == GVOTE_BF16 && (sh->head_dim == 64 || sh->head_dim == 128) && mode == GVOTE_SELECT_TOPP &&
-         p < 1.0f && NQ >= 1;
+  if (sh->dtype != GVOTE_BF16 || (sh->head_dim != 64 && sh->head_dim != 128) || NQ < 1) return false;
+  return mode == GVOTE_SELECT_TOPK || (mode == GVOTE_SELECT_TOPP && p < 1.0f);
 }
 
 FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S) {
@@ -934,7 +947,8 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
 }
 
 gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, int n_items, int S, const void *q,
-                               float p, uint32_t *rowmask, float *row_max, float *row_sum, void *ws, hipStream_t st) {
+                               float p, int mode, const int *k_per_row, uint32_t *rowmask, float *row_max,
+                               float *row_sum, void *ws, hipStream_t st) {
   const FastPlan pl = plan_fast(sh, items, n_items, S);
   char *wsb = reinterpret_cast<char *>(ws);
   const int G = sh->n_q_heads / sh->n_kv_heads;
@@ -952,7 +966,8 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.c2 = tab.scale * 1.44269504088896340736f;
     tab.p = p;
     tab.spin_limit = g_spin_limit;
-    tab.q = q; tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
+    tab.q = q; tab.k_per_row = k_per_row; tab.mode = mode;
+    tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.n_list = reinterpret_cast<int *>(wsb) + 1;
     tab.row_list = reinterpret_cast<int *>(wsb + pl.off_list);
@@ -980,19 +995,22 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       part += sh->n_kv_heads * f.n_chunks;
       mask_off += (long long)tab.rows_per_item * f.W;
     }
-    tab.emit_split = emit_split_of(tab.chunk_keys); tab.pad4 = 0;
+    tab.emit_split = emit_split_of(tab.chunk_keys);
     tab.sub_per_row = most_chunks * tab.emit_split * 2 * kWaves;
     tab.n_slots = part;
     const int grid_wg = tab.NQB == 1 ? wg : ceil_div(part, 8) * 8 * tab.NQB;
     const int rows = nb * tab.rows_per_item;
+    const bool topk = mode == GVOTE_SELECT_TOPK;
     if (sh->head_dim == 128) {
-      hipLaunchKernelGGL(score_hist_kernel<128>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      if (topk) hipLaunchKernelGGL((score_hist_kernel<128, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      else hipLaunchKernelGGL((score_hist_kernel<128, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
     } else {
-      hipLaunchKernelGGL(score_hist_kernel<64>, dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      if (topk) hipLaunchKernelGGL((score_hist_kernel<64, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
+      else hipLaunchKernelGGL((score_hist_kernel<64, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
@@ -1004,7 +1022,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     hipLaunchKernelGGL((resolve_kernel<kCandCap, true>), dim3(rows), dim3(64), 0, st, tab, rows);
     GVOTE_CHECK_LAUNCH();
     // rows the histogram could not settle are redone exactly
-    gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, GVOTE_SELECT_TOPP, nullptr, rowmask,
+    gvote_status stt = launch_select_rows_general(sh, items + b0, nb, b0, S, q, p, mode, k_per_row, rowmask,
                                                   batch_mask_off0, row_max, row_sum, tab.row_list, tab.n_list,
                                                   tab.n_fallback, reinterpret_cast<float *>(wsb + pl.ws_bytes),
                                                   general_cache_bytes(items, n_items), st);

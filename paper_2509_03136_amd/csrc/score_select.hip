@@ -323,7 +323,7 @@ gvote_status launch_score_select(const gvote_shape *sh, const gvote_item *items,
   (void)ws_bytes;
   bool fast = fast_path_ok(sh, S, mode, p);
   for (int i = 0; i < n_items && fast; ++i) fast = items[i].L >= 32;   // the matrix-core path loads whole 32-key tiles
-  if (fast) return launch_score_fast(sh, items, n_items, S, q, p, rowmask, row_max, row_sum, ws, st);
+  if (fast) return launch_score_fast(sh, items, n_items, S, q, p, mode, k_per_row, rowmask, row_max, row_sum, ws, st);
   long long mask_off = 0;
   const size_t cache_bytes = ws ? general_cache_bytes(items, n_items) : 0;
   for (int b0 = 0; b0 < n_items; b0 += kMaxItems) {

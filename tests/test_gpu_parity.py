@@ -284,7 +284,8 @@ def test_select_topk_mode(g):
     ref = U.oracle_item(wl, it)
     R = wl.S * wl.n_q_heads
     ks = (np.arange(R) * 37 % 720) - 5          # includes k < 1 and k > L (clamped to [1, L])
-    gm, _ = _select_case(g, wl, [it], ref["q_tilde"][None], 0.5, mode=1, k_per_row=ks)
+    gm, pipe = _select_case(g, wl, [it], ref["q_tilde"][None], 0.5, mode=1, k_per_row=ks)
+    say(f"  TopK with k up to L: {pipe.fallback_rows()} of {R} rows redone by the exact selector (cut below the window)")
     lg = ref["logits"].reshape(R, -1)
     gm = gm.reshape(R, -1)
     bad = 0
@@ -471,6 +472,10 @@ def test_algorithm1_mode_real_query_budget_then_topk(g):
     pipe = g.Pipeline(b, S, p)
     pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
     g.score_select(b, S, pipe.q, p, pipe.rowmask, mode=g.SELECT_TOPK, k_per_row=counts, ws=pipe.ws)
+    torch.cuda.synchronize()
+    n_fb = pipe.fallback_rows()          # TopK runs on the matrix-core path too (count-weighted histogram)
+    say(f"  TopK rows redone by the exact selector: {n_fb} of {n * S * hq} {pipe.fallback_reasons()}")
+    assert n_fb <= n * S * hq // 20
     pipe.compact()
     torch.cuda.synchronize()
     counts_h = counts.cpu().numpy()
