@@ -235,7 +235,7 @@ struct FastItem {
   const void *k;
   long long tok_stride, head_stride;
   long long mask_off;
-  long long tmax0;  // first float of the item's [H_kv][W][NQ] tile maxima
+  long long tmax0;  // first entry of the item's [H_kv][W][NQ] tile bins
   int L, W;
   int n_chunks;     // key chunks per KV head
   int wg0;          // first workgroup of the item
@@ -258,7 +258,7 @@ struct FastTable {
   float *part_max;          // [slot][NQ]: chunk maximum of the raw dot
   int *part_top;            // [slot][NQ]: top (absolute bin) of the chunk's histogram window
   uint32_t *part_hist;      // [slot][NQ][kBins]: fixed-point bin weights; last bin: a float's bits
-  float *tile_max;          // per (item, KV head, 32-key tile, row): maximum raw dot, written by pass 1
+  short *tile_bin;          // per (item, KV head, 32-key tile, row): bin of the largest raw dot, written by pass 1
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
   int *n_list;              // rows of this batch waiting for the general selector (second word) ...

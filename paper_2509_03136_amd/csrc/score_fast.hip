@@ -71,6 +71,8 @@ __device__ __forceinline__ void lds_add_u32(uint32_t byte_addr, uint32_t v) {
   (void)byte_addr; (void)v;
 #endif
 }
+typedef __attribute__((address_space(3))) int lds_int;    // (workgroup flags are polled with LDS loads: a generic-
+                                                          // pointer load would also wait for every global load in flight)
 // byte offset of an LDS object inside the workgroup's LDS
 __device__ __forceinline__ int lds_offset(const void *p) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -235,8 +237,8 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
   const float c1 = tab.c1, c2 = tab.c2;
   const float ebias = (float)kFixBits - kLog2ePerBin;
   uint32_t *hrow[2] = {hist + col * (kBins + 1), hist + (32 + col) * (kBins + 1)};
-  volatile int *pending = &S->pending;
-  volatile int *done = &S->done;
+  volatile lds_int *pending = (volatile lds_int *)(size_t)lds_offset(&S->pending);
+  volatile lds_int *done = (volatile lds_int *)(size_t)lds_offset(&S->done);
   int top[2] = {kTopUnset, kTopUnset};      // this lane's copy of its two rows' window tops
   float mxrun[2] = {-INFINITY, -INFINITY};
 
@@ -311,13 +313,14 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
     mx1 = fmaxf(mx1, __shfl_xor(mx1, 32, 64));
     mxrun[0] = fmaxf(mxrun[0], mx0);
     mxrun[1] = fmaxf(mxrun[1], mx1);
-    if (lane < 32) {        // per (tile, row) maxima: pass 2 skips tiles no row needs
-      float *tm = tab.tile_max + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5) + tile) * tab.NQ + c.n0 + col;
-      if (c.n0 + col < tab.NQ) tm[0] = mx0;
-      if (TWO && c.n0 + 32 + col < tab.NQ) tm[32] = mx1;
+    const int amx0 = (int)floorf(mx0 * c1), amx1 = TWO ? (int)floorf(mx1 * c1) : 0;
+    if (lane < 32) {        // bin of the largest dot of every (tile, row): pass 2 skips tiles no row needs
+      short *tm = tab.tile_bin + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5) + tile) * tab.NQ + c.n0 + col;
+      if (c.n0 + col < tab.NQ) tm[0] = (short)max(-32768, min(32767, amx0));      // (clamping only ever keeps a tile)
+      if (TWO && c.n0 + 32 + col < tab.NQ) tm[32] = (short)max(-32768, min(32767, amx1));
     }
-    const bool over0 = (int)floorf(mx0 * c1) > top[0];
-    const bool over1 = TWO && (int)floorf(mx1 * c1) > top[1];
+    const bool over0 = amx0 > top[0];
+    const bool over1 = TWO && amx1 > top[1];
     bool event = __any(over0 || over1);          // wave-uniform
     if (event) {
       if (lane < 32) {
@@ -574,22 +577,22 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
   const int nk = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave (<= 32)
 
-  // which of my tiles can hold a key at or above some row's cut bin (half a bin of margin)?
+  // which of my tiles hold a key in or above some row's cut bin?  (a = floor(d c1) is monotone in d, so the
+  // bin of a tile's largest dot says it exactly)
   uint32_t need = 0u;
   {
-    const int a_l = E->astar[lane];
-    const float dcut_l = a_l == 0x7FFFFFFF ? INFINITY : ((float)a_l - 0.5f) / c1;
-    const float *tm = tab.tile_max + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5)) * tab.NQ + c.n0 + lane;
+    const int a_l = E->astar[lane];      // 0x7FFFFFFF for absent rows and rows the exact selector redoes
+    const short *tm = tab.tile_bin + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5)) * tab.NQ + c.n0 + lane;
     const bool row_ok = c.n0 + lane < tab.NQ;
     // all loads first (independent, in flight together), then the votes
     constexpr int kMaxK = 32;          // chunk_keys <= 8192 -> at most 32 tiles per wave
-    float v[kMaxK];
+    int v[kMaxK];
 #pragma unroll
     for (int k = 0; k < kMaxK; ++k)
-      v[k] = (row_ok && k < nk) ? tm[(size_t)(wave + kWaves * k) * tab.NQ] : -INFINITY;
+      v[k] = (row_ok && k < nk) ? (int)tm[(size_t)(wave + kWaves * k) * tab.NQ] : -32768;
 #pragma unroll
     for (int k = 0; k < kMaxK; ++k)
-      if (__any(v[k] >= dcut_l)) need |= 1u << k;
+      if (__any(v[k] >= a_l)) need |= 1u << k;
   }
 
   // Candidate sub-lists: one per (row, key chunk, wave, lane half), written by exactly one lane, so the
@@ -939,7 +942,7 @@ FastPlan plan_fast(const gvote_shape *sh, const gvote_item *items, int n_items, 
   pl.off_cnt = pl.off_info + align_up(max_rows * sizeof(RowInfo), 256);
   pl.off_cands = pl.off_cnt + align_up(max_rows * max_sub * sizeof(int), 256);
   pl.off_tmax = pl.off_cands + align_up(max_rows * max_sub * kSubCap * sizeof(uint2), 256);
-  pl.off_list = pl.off_tmax + align_up(max_tiles * NQ * sizeof(float), 256);
+  pl.off_list = pl.off_tmax + align_up(max_tiles * NQ * sizeof(short), 256);
   pl.off_ovfc = pl.off_list + align_up(max_rows * sizeof(int), 256);
   pl.off_ovf = pl.off_ovfc + align_up(max_rows * sizeof(int), 256);
   pl.ws_bytes = pl.off_ovf + align_up(max_rows * kOvfCap * sizeof(uint2), 256);
@@ -975,7 +978,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.ovf = reinterpret_cast<uint2 *>(wsb + pl.off_ovf);
     tab.part_max = reinterpret_cast<float *>(wsb + pl.off_max);
     tab.part_top = reinterpret_cast<int *>(wsb + pl.off_top);
-    tab.tile_max = reinterpret_cast<float *>(wsb + pl.off_tmax);
+    tab.tile_bin = reinterpret_cast<short *>(wsb + pl.off_tmax);
     tab.part_hist = reinterpret_cast<uint32_t *>(wsb + pl.off_hist);
     tab.info = reinterpret_cast<RowInfo *>(wsb + pl.off_info);
     tab.cand_cnt = reinterpret_cast<int *>(wsb + pl.off_cnt);
