@@ -173,6 +173,10 @@ def main():
     ap.add_argument("--S", type=int, default=0, help="override the number of synthetic queries")
     ap.add_argument("--p", type=float, default=0.0, help="override the mass threshold")
     ap.add_argument("--sweep", choices=["S", "p"], default=None, help="Sec. 4.4 cost trends: vary S or p")
+    ap.add_argument("--alg1", action="store_true",
+                    help="also time Algorithm 1 as printed: top-p of one real query per head -> B_step -> row-wise "
+                         "TopK of the synthetic rows -> union / compaction (the first synthetic sample stands in "
+                         "for the real current query)")
     ap.add_argument("--cpu-sample", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -259,6 +263,35 @@ def main():
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,
     }
+    if args.alg1:
+        n, S, hq = wl.n_items, wl.S, wl.n_q_heads
+        q0 = pipe.q[:, :1].contiguous()
+        mask0 = torch.empty(sum(hq * b.words(i) for i in range(n)), device=dev, dtype=torch.int32)
+        counts = torch.empty(n, S, hq, device=dev, dtype=torch.int32)
+
+        def alg1_select():
+            g.score_select(b, 1, q0, wl.p, mask0, ws=pipe.ws)
+            g.count_rows(b, 1, mask0, S, counts)
+            g.score_select(b, S, pipe.q, wl.p, pipe.rowmask, mode=g.SELECT_TOPK, k_per_row=counts, ws=pipe.ws)
+
+        for _ in range(2):
+            alg1_select()
+            pipe.compact()
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = max(3, args.steps // 2)
+        t_sel = t_cmp = 0.0
+        for _ in range(reps):
+            e[0].record(); alg1_select(); e[1].record(); pipe.compact(); e[2].record()
+            torch.cuda.synchronize()
+            t_sel += e[0].elapsed_time(e[1]); t_cmp += e[1].elapsed_time(e[2])
+        g.score_select(b, S, pipe.q, wl.p, pipe.rowmask, mode=g.SELECT_TOPK, k_per_row=counts, ws=pipe.ws)
+        torch.cuda.synchronize()
+        out["alg1"] = {"select_ms": t_sel / reps, "compact_ms": t_cmp / reps,
+                       "ms_per_step": stage_ms["fit"] + stage_ms["sample"] + (t_sel + t_cmp) / reps,
+                       "topk_fallback_rows": pipe.fallback_rows(),
+                       "kept_fraction": int(pipe.offsets[-1].item()) / float(tok * wl.n_kv_heads),
+                       "mean_B_step": float(counts.float().mean().item())}
     if args.sweep:
         values = {"S": [4, 8, 16, 32, 64], "p": [0.5, 0.8, 0.9, 0.95, 0.99]}[args.sweep]
         rows = []

@@ -169,3 +169,43 @@ def test_config5_ragged_batch(g):
     say(f"  boundary keys: {own} own, {e2e} end to end; fallback rows {pipe.n_fallback}; usage per request", np.round(usage, 3).tolist())
     assert own <= 8
     assert usage.max() > 2 * usage.min()          # the adaptive budgets really differ across requests
+
+
+def test_context_beyond_128k_single_item(g):
+    """One Llama-3-8B-shaped layer at L = 262144 (twice the length at which the paper reports that the
+    S x L logits matrix runs out of memory, Sec. 4.4): nothing of that size is ever stored here.  Sampled
+    rows are compared on the GPU's own stored queries (full sandwich), the fit on sampled channels."""
+    L = 262144
+    wl = W.scaled(W.config(3), lengths=(L,), n_planted=(4096,))
+    say(f"long context: 1 layer x {L}")
+    items, pipe = _run(g, wl)
+    _structure_checks(wl, items, pipe, sample_items=())
+    it = items[0]
+    # Gaussian fit on sampled channels (the oracle's two-pass fp64 statistics)
+    ch = torch.arange(7, wl.d, 131, device=DEV)
+    hid = it["hidden"][:, ch].to(torch.float32).cpu().numpy()
+    mu, var = O.fit_gaussian(hid, wl.n_skip, wl.ddof)
+    gmu, gvar = pipe.mu[0][ch].cpu().numpy(), pipe.var[0][ch].cpu().numpy()
+    assert np.all(np.abs(gmu - mu) <= 1e-5 * np.maximum(np.abs(mu), np.sqrt(var)) + 1e-7)
+    assert np.all(np.abs(gvar - var) <= 1e-5 * var + 1e-9)
+    # sampled rows of three KV groups
+    k = U.f32np(it["k"].cpu())
+    q_own = U.f32np(pipe.q[0]).astype(np.float64)
+    gm_words = pipe.rowmask.cpu().numpy().view(np.uint32).reshape(pipe.rows, -1)
+    p = U.p32(wl.p)
+    boundary = 0
+    for kvh, ss in ((0, (0, 9)), (3, (4,)), (7, (15, 2))):
+        heads = list(range(kvh * wl.group, (kvh + 1) * wl.group))
+        for s in ss:
+            rows = [s * wl.n_q_heads + h for h in heads]
+            gm = O.unpack_mask_words(gm_words[rows], L)[None]                      # [1, G, L]
+            lg = O.scores(q_own[s:s + 1][:, heads], k[:, kvh:kvh + 1, :])
+            boundary += U.check_rowmask_strict(gm, lg, p, U.STAGE_TOL[wl.dtype])
+            m = lg.max(-1).reshape(-1)
+            gmax = pipe.row_max[0].cpu().numpy()[rows]
+            assert np.all(np.abs(gmax - m) <= U.STAGE_TOL[wl.dtype] * (1 + np.abs(m)))
+    rho = float(pipe.offsets[-1].item()) / (L * wl.n_kv_heads)
+    ws_mib = pipe.ws.numel() / 2 ** 20
+    say(f"  boundary keys {boundary} (20 rows); kept fraction {rho:.4f}; fallback rows {pipe.n_fallback} {pipe.fallback_why}; "
+        f"workspace {ws_mib:.0f} MiB (an S x H_q x L fp32 logits matrix would be {wl.S * wl.n_q_heads * L * 4 / 2 ** 20:.0f} MiB)")
+    assert boundary <= 4
