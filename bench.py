@@ -173,6 +173,8 @@ def main():
     ap.add_argument("--S", type=int, default=0, help="override the number of synthetic queries")
     ap.add_argument("--p", type=float, default=0.0, help="override the mass threshold")
     ap.add_argument("--sweep", choices=["S", "p"], default=None, help="Sec. 4.4 cost trends: vary S or p")
+    ap.add_argument("--consumer", action="store_true",
+                    help="also time one decode-attention step over the compressed cache (Sec. 3.4's consumer)")
     ap.add_argument("--alg1", action="store_true",
                     help="also time Algorithm 1 as printed: top-p of one real query per head -> B_step -> row-wise "
                          "TopK of the synthetic rows -> union / compaction (the first synthetic sample stands in "
@@ -263,6 +265,26 @@ def main():
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,
     }
+    if args.consumer:
+        qd = torch.randn(wl.n_items, wl.n_q_heads, wl.d_k, device=dev, dtype=torch.float32).to(pipe.q.dtype)
+        od = torch.empty_like(qd)
+        lse = torch.empty(wl.n_items, wl.n_q_heads, device=dev, dtype=torch.float32)
+        for _ in range(3):
+            g.decode_attention(b, qd, pipe.k_out, pipe.v_out, pipe.offsets, od, pipe.ws, lse)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            g.decode_attention(b, qd, pipe.k_out, pipe.v_out, pipe.offsets, od, pipe.ws, lse)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        cache_bytes = kept * wl.d_k * wl.elem_bytes * 2
+        out["consumer"] = {"decode_attention_ms": ms, "compressed_cache_bytes": cache_bytes,
+                           "achieved_GBs": cache_bytes / (ms * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": cache_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "full_cache_bytes": tok * wl.n_kv_heads * wl.d_k * wl.elem_bytes * 2}
     if args.alg1:
         n, S, hq = wl.n_items, wl.S, wl.n_q_heads
         q0 = pipe.q[:, :1].contiguous()

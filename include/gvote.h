@@ -203,10 +203,13 @@ GVOTE_API gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_it
  * (dtype); head h of item i attends to rows offsets[i*n_kv_heads + h/G] .. offsets[.. + 1] - 1 of the packed
  * k_out / v_out that gvote_union_compact produced:  out[i, h, :] = softmax(q K^T / sqrt(head_dim)) V, rounded
  * to dtype ([n_items, n_q_heads, head_dim]); lse[i, h] (fp32, optional) = log sum exp of the logits.
- * head_dim * element size / 16 must be a power of two <= 64 (else GVOTE_ERR_UNSUPPORTED). */
+ * head_dim * element size / 16 must be a power of two <= 64 (else GVOTE_ERR_UNSUPPORTED).
+ * ws: gvote_decode_workspace_bytes(shape, n_items) bytes (also covered by gvote_workspace_bytes for the same
+ * n_items): the packed rows of a head are shared out over several workgroups whose partial results meet there. */
 GVOTE_API gvote_status gvote_decode_attention(const gvote_shape *shape, int32_t n_items, const void *q,
                                               const void *k_out, const void *v_out, const int64_t *offsets,
-                                              void *out, float *lse, void *stream);
+                                              void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
+GVOTE_API size_t gvote_decode_workspace_bytes(const gvote_shape *shape, int32_t n_items);
 
 /* Sec. 3.3 "Attention Overlap": overlap[i, s, h] (fp32, [n_items, S, n_q_heads]) = the share of the REAL query
  * q_real[i, h, :]'s attention (softmax over all L keys of KV head h/G) that falls on the keys selected in row

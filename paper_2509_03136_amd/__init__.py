@@ -6,7 +6,7 @@ in the HIP kernels of the library.  PyTorch is used for device memory and stream
 """
 from .binding import (  # noqa: F401
     GVoteError, Shape, Item, Batch, lib, lib_path, abi_version, status_string, workspace_bytes,
-    fit_gaussian, sample_queries, score_select, union_compact, union_compact_static, count_rows, decode_attention, attention_overlap,
+    fit_gaussian, sample_queries, score_select, union_compact, union_compact_static, count_rows, decode_attention, decode_workspace_bytes, attention_overlap,
     philox_u32, debug_set_spin_limit, Pipeline,
     SELECT_TOPP, SELECT_TOPK, F32, BF16,
 )

@@ -70,7 +70,9 @@ def lib() -> C.CDLL:
     L.gvote_count_rows.restype = C.c_int
     L.gvote_count_rows.argtypes = [sp, ip, i32, i32, vp, i32, vp, vp]
     L.gvote_decode_attention.restype = C.c_int
-    L.gvote_decode_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.gvote_decode_attention.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.gvote_decode_workspace_bytes.restype = sz
+    L.gvote_decode_workspace_bytes.argtypes = [sp, i32]
     L.gvote_attention_overlap.restype = C.c_int
     L.gvote_attention_overlap.argtypes = [sp, ip, i32, i32, vp, vp, vp, vp, sz, vp]
     L.gvote_debug_set_spin_limit.restype = i32
@@ -200,10 +202,15 @@ def count_rows(b: Batch, S: int, rowmask: torch.Tensor, repeat: int, counts: tor
                                   _stream(stream)), "gvote_count_rows")
 
 
+def decode_workspace_bytes(b: Batch) -> int:
+    return int(lib().gvote_decode_workspace_bytes(C.byref(b.shape), b.n_items))
+
+
 def decode_attention(b: Batch, q: torch.Tensor, k_out: torch.Tensor, v_out: torch.Tensor, offsets: torch.Tensor,
-                     out: torch.Tensor, lse: Optional[torch.Tensor] = None, stream=None) -> None:
+                     out: torch.Tensor, ws: torch.Tensor, lse: Optional[torch.Tensor] = None, stream=None) -> None:
     _check(lib().gvote_decode_attention(C.byref(b.shape), b.n_items, _ptr(q), _ptr(k_out), _ptr(v_out), _ptr(offsets),
-                                        _ptr(out), _ptr(lse), _stream(stream)), "gvote_decode_attention")
+                                        _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
+                                        _stream(stream)), "gvote_decode_attention")
 
 
 def attention_overlap(b: Batch, S: int, q_real: torch.Tensor, rowmask: torch.Tensor, overlap: torch.Tensor,

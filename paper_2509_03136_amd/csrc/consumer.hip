@@ -2,11 +2,13 @@
 // variable-length attention interface; Eq. (1)-(2)), and the attention-overlap diagnostic of Sec. 3.3.
 //
 //   decode_attention   one decode query per head against the packed rows of its KV head:
-//                      softmax(q K^T / sqrt(d_k)) V.  One workgroup per (item, KV head) serves the G query
-//                      heads of the group, so every packed K/V row is read once; rows are contiguous in
-//                      the packed cache: a key row is read by d_k*elem/16 neighbouring lanes, 16 bytes each;
-//                      online softmax per lane group, merged across the wave by shuffles and across the
-//                      workgroup through LDS.  Memory-bound (2 * B * d_k * elem bytes per KV head).
+//                      softmax(q K^T / sqrt(d_k)) V.  The packed rows of a head are split over several
+//                      workgroups (so that few heads still fill the chip); each serves the G query heads of
+//                      the group over its share, so every packed K/V row is read once; rows are contiguous
+//                      in the packed cache: a key row is read by d_k*elem/16 neighbouring lanes, 16 bytes
+//                      each, four row steps in flight; online softmax per lane group, merged across the wave
+//                      by shuffles, across the workgroup through LDS, across the shares by a small merge
+//                      kernel through their log-sum-exp.  Memory-bound (2 * B * d_k * elem bytes per KV head).
 //   attention_overlap  how much of a REAL query's attention falls on the key set a synthetic row chose:
 //                      per (item, query head) the real query's logits over all L keys (kept in the
 //                      workspace), their softmax, and for every sample s the weight inside row (s, h)'s mask.
@@ -17,16 +19,21 @@ namespace gvote {
 namespace {
 
 constexpr int kGMax = 8;    // query heads of a group handled per sweep over the packed rows
+constexpr int kRowsInFlight = 4;   // row steps a lane loads before it consumes them
 
 struct DecodeArgs {
   const void *q, *k_out, *v_out;
   const long long *offsets;
   void *out;
   float *lse;
-  int n_q_heads, n_kv_heads, head_dim;
-  float scale;
+  float *part;              // workspace: [item * H_q + h][split][d_k + 2]: un-normalised output, row maximum, weight sum
+  int n_q_heads, n_kv_heads, head_dim, n_splits;
+  float scale;              // log2(e) / sqrt(d_k): logits are kept in log2 units, weights are powers of two
 };
 
+// grid (item * H_kv + kv head, split): one workgroup serves the G query heads of the group over ITS SHARE of the
+// head's packed rows (several workgroups per head keep the whole chip streaming even with few heads); the shares
+// are merged by decode_merge_kernel through their log-sum-exp.
 template <typename T>
 __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs a) {
   constexpr int NV = Vec16<T>::N;
@@ -36,9 +43,11 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int piece = lane % ppr, rs = lane / ppr;
   const int hh = blockIdx.x;                     // item * H_kv + kv head
+  const int split = blockIdx.y;
   const int item = hh / a.n_kv_heads, kvh = hh - item * a.n_kv_heads;
   const int G = a.n_q_heads / a.n_kv_heads;
-  const long long lo = a.offsets[hh], hi = a.offsets[hh + 1];
+  const long long lo_h = a.offsets[hh], n_h = a.offsets[hh + 1] - lo_h;
+  const long long lo = lo_h + n_h * split / a.n_splits, hi = lo_h + n_h * (split + 1) / a.n_splits;
   const T *kb = reinterpret_cast<const T *>(a.k_out);
   const T *vb = reinterpret_cast<const T *>(a.v_out);
   __shared__ float part[4][kGMax][256 + 2];      // per wave: acc[d_k], m, l of every head of the sweep
@@ -57,28 +66,35 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs 
         Vec16<T>::load(qrow + piece * NV, qv[g]);
       }
     }
-    for (long long r0 = lo + (long long)wave * rps; r0 < hi; r0 += 4 * rps) {
-      const long long r = r0 + rs;
-      const bool valid = r < hi;
-      const long long rc = valid ? r : hi - 1;   // in bounds; the contribution is dropped
-      float kv[NV], vv[NV];
-      Vec16<T>::load(kb + rc * dk + piece * NV, kv);
-      Vec16<T>::load(vb + rc * dk + piece * NV, vv);
+    // kRowsInFlight row steps are loaded (K and V, 16 bytes per lane each) before any is consumed
+    for (long long r0 = lo + (long long)wave * rps; r0 < hi; r0 += 4 * rps * kRowsInFlight) {
+      float kv[kRowsInFlight][NV], vv[kRowsInFlight][NV];
 #pragma unroll
-      for (int g = 0; g < kGMax; ++g) {
-        if (g < ng) {
-          float s = 0.f;
+      for (int u = 0; u < kRowsInFlight; ++u) {
+        const long long r = r0 + (long long)u * 4 * rps + rs;
+        const long long rc = r < hi ? r : hi - 1;          // in bounds (hi > lo here); the contribution is dropped
+        Vec16Stream<T>::load(kb + rc * dk + piece * NV, kv[u]);
+        Vec16Stream<T>::load(vb + rc * dk + piece * NV, vv[u]);
+      }
 #pragma unroll
-          for (int i = 0; i < NV; ++i) s = fmaf(qv[g][i], kv[i], s);
-          for (int off = ppr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-          s *= a.scale;
-          if (valid) {
-            const float mn = fmaxf(m[g], s);
-            const float corr = expf(m[g] - mn), pw = expf(s - mn);     // expf(-inf) = 0 on the first row
-            l[g] = l[g] * corr + pw;
+      for (int u = 0; u < kRowsInFlight; ++u) {
+        const bool valid = r0 + (long long)u * 4 * rps + rs < hi;
 #pragma unroll
-            for (int i = 0; i < NV; ++i) acc[g][i] = fmaf(acc[g][i], corr, pw * vv[i]);
-            m[g] = mn;
+        for (int g = 0; g < kGMax; ++g) {
+          if (g < ng) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) s = fmaf(qv[g][i], kv[u][i], s);
+            for (int off = ppr >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            s *= a.scale;
+            if (valid) {
+              const float mn = fmaxf(m[g], s);
+              const float corr = __builtin_amdgcn_exp2f(m[g] - mn), pw = __builtin_amdgcn_exp2f(s - mn);     // 2^(-inf) = 0 on the first row
+              l[g] = l[g] * corr + pw;
+#pragma unroll
+              for (int i = 0; i < NV; ++i) acc[g][i] = fmaf(acc[g][i], corr, pw * vv[u][i]);
+              m[g] = mn;
+            }
           }
         }
       }
@@ -90,7 +106,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs 
         for (int off = ppr; off < 64; off <<= 1) {
           const float mo = __shfl_xor(m[g], off, 64), lo2 = __shfl_xor(l[g], off, 64);
           const float mn = fmaxf(m[g], mo);
-          const float ca = mn == -INFINITY ? 0.f : expf(m[g] - mn), cb = mn == -INFINITY ? 0.f : expf(mo - mn);
+          const float ca = mn == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[g] - mn), cb = mn == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
           l[g] = l[g] * ca + lo2 * cb;
 #pragma unroll
           for (int i = 0; i < NV; ++i) acc[g][i] = acc[g][i] * ca + __shfl_xor(acc[g][i], off, 64) * cb;
@@ -104,22 +120,49 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs 
       }
     }
     __syncthreads();
-    for (int o = threadIdx.x; o < ng * dk; o += 256) {
-      const int g = o / dk, ch = o - g * dk;
+    for (int o = threadIdx.x; o < ng * (dk + 2); o += 256) {
+      const int g = o / (dk + 2), ch = o - g * (dk + 2);
       float mn = -INFINITY;
       for (int w = 0; w < 4; ++w) mn = fmaxf(mn, part[w][g][256]);
-      float num = 0.f, den = 0.f;
-      for (int w = 0; w < 4; ++w) {
-        const float cw = part[w][g][256] == -INFINITY ? 0.f : expf(part[w][g][256] - mn);
-        num = fmaf(part[w][g][ch], cw, num);
-        den = fmaf(part[w][g][257], cw, den);
+      float val;
+      if (ch == dk) {
+        val = mn;
+      } else {
+        val = 0.f;
+        for (int w = 0; w < 4; ++w) {
+          const float cw = part[w][g][256] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(part[w][g][256] - mn);
+          val = fmaf(part[w][g][ch < dk ? ch : 257], cw, val);
+        }
       }
       const size_t row = (size_t)item * a.n_q_heads + kvh * G + g0 + g;
-      reinterpret_cast<T *>(a.out)[row * dk + ch] = from_f32<T>(den > 0.f ? num / den : 0.f);
-      if (ch == 0 && a.lse) a.lse[row] = den > 0.f ? mn + logf(den) : -INFINITY;
+      a.part[(row * a.n_splits + split) * (dk + 2) + ch] = val;      // ch < dk: numerator; dk: maximum; dk + 1: weight sum
     }
     __syncthreads();
   }
+}
+
+// one workgroup per (item, query head): out = sum_s e^(m_s - m) num_s / sum_s e^(m_s - m) l_s
+template <typename T>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
+  const size_t row = blockIdx.x;
+  const int dk = a.head_dim;
+  const float *p = a.part + row * a.n_splits * (dk + 2);
+  float mn = -INFINITY;
+  for (int s = 0; s < a.n_splits; ++s) mn = fmaxf(mn, p[s * (dk + 2) + dk]);
+  float den = 0.f;
+  for (int s = 0; s < a.n_splits; ++s) {
+    const float ms = p[s * (dk + 2) + dk];
+    den = fmaf(p[s * (dk + 2) + dk + 1], ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - mn), den);
+  }
+  for (int ch = threadIdx.x; ch < dk; ch += 256) {
+    float num = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) {
+      const float ms = p[s * (dk + 2) + dk];
+      num = fmaf(p[s * (dk + 2) + ch], ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - mn), num);
+    }
+    reinterpret_cast<T *>(a.out)[row * dk + ch] = from_f32<T>(den > 0.f ? num / den : 0.f);
+  }
+  if (threadIdx.x == 0 && a.lse) a.lse[row] = den > 0.f ? (mn + log2f(den)) * 0.69314718055994530942f : -INFINITY;
 }
 
 // ---------------------------------------------------------------- attention overlap
@@ -221,18 +264,37 @@ size_t overlap_ws_bytes(const gvote_shape *sh, const gvote_item *items, int n_it
   return worst * sizeof(float);
 }
 
+int decode_splits(const gvote_shape *sh, int n_items) {
+  // about eight workgroups per CU over the call, at most 64 shares per head
+  const int heads = n_items * sh->n_kv_heads;
+  int s = (2048 + heads - 1) / heads;
+  return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+
+size_t decode_ws_bytes(const gvote_shape *sh, int n_items) {
+  return (size_t)n_items * sh->n_q_heads * decode_splits(sh, n_items) * (sh->head_dim + 2) * sizeof(float);
+}
+
 gvote_status launch_decode_attention(const gvote_shape *sh, int n_items, const void *q, const void *k_out,
-                                     const void *v_out, const long long *offsets, void *out, float *lse,
+                                     const void *v_out, const long long *offsets, void *out, float *lse, void *ws,
                                      hipStream_t st) {
   DecodeArgs a;
   a.q = q; a.k_out = k_out; a.v_out = v_out; a.offsets = offsets; a.out = out; a.lse = lse;
+  a.part = reinterpret_cast<float *>(ws);
   a.n_q_heads = sh->n_q_heads; a.n_kv_heads = sh->n_kv_heads; a.head_dim = sh->head_dim;
-  a.scale = (float)(1.0 / sqrt((double)sh->head_dim));
-  const dim3 grid(n_items * sh->n_kv_heads);
-  if (sh->dtype == GVOTE_F32)
+  a.n_splits = decode_splits(sh, n_items);
+  a.scale = (float)(1.44269504088896340736 / sqrt((double)sh->head_dim));
+  const dim3 grid(n_items * sh->n_kv_heads, a.n_splits);
+  const dim3 gridm(n_items * sh->n_q_heads);
+  if (sh->dtype == GVOTE_F32) {
     hipLaunchKernelGGL(decode_attention_kernel<float>, grid, dim3(256), 0, st, a);
-  else
+    GVOTE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(decode_merge_kernel<float>, gridm, dim3(256), 0, st, a);
+  } else {
     hipLaunchKernelGGL(decode_attention_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+    GVOTE_CHECK_LAUNCH();
+    hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, gridm, dim3(256), 0, st, a);
+  }
   GVOTE_CHECK_LAUNCH();
   return GVOTE_OK;
 }

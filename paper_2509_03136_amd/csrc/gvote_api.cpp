@@ -56,6 +56,7 @@ size_t workspace_bytes_unchecked(const gvote_shape *sh, const gvote_item *items,
   w = max_sz(w, plan_score(sh, items, n_items, S).ws_bytes);
   w = max_sz(w, plan_union(sh, items, n_items).ws_bytes);
   w = max_sz(w, overlap_ws_bytes(sh, items, n_items));
+  w = max_sz(w, decode_ws_bytes(sh, n_items));
   return align_up(w, 256) + 256;
 }
 
@@ -76,7 +77,7 @@ const char *gvote_status_string(gvote_status st) {
   return "unknown status";
 }
 
-int32_t gvote_abi_version(void) { return 1000; }
+int32_t gvote_abi_version(void) { return 1001; }
 
 size_t gvote_workspace_bytes(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S) {
   if (check_shape(shape) != GVOTE_OK || S < 1 || S > 128) return 0;
@@ -184,15 +185,22 @@ gvote_status gvote_count_rows(const gvote_shape *shape, const gvote_item *items,
 }
 
 gvote_status gvote_decode_attention(const gvote_shape *shape, int32_t n_items, const void *q, const void *k_out,
-                                    const void *v_out, const int64_t *offsets, void *out, float *lse, void *stream) {
+                                    const void *v_out, const int64_t *offsets, void *out, float *lse, void *ws,
+                                    size_t ws_bytes, void *stream) {
   gvote_status st = check_shape(shape);
   if (st != GVOTE_OK) return st;
-  if (n_items < 1 || !q || !k_out || !v_out || !offsets || !out) return GVOTE_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k_out) || !aligned16(v_out) || !aligned16(out)) return GVOTE_ERR_SHAPE;
+  if (n_items < 1 || !q || !k_out || !v_out || !offsets || !out || !ws) return GVOTE_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_out) || !aligned16(v_out) || !aligned16(out) || !aligned16(ws)) return GVOTE_ERR_SHAPE;
   const int ppr = shape->head_dim * (int)elem_bytes(shape->dtype) / 16;
   if (ppr < 1 || ppr > 64 || (ppr & (ppr - 1))) return GVOTE_ERR_UNSUPPORTED;
+  if (ws_bytes < decode_ws_bytes(shape, n_items)) return GVOTE_ERR_WORKSPACE;
   return launch_decode_attention(shape, n_items, q, k_out, v_out, reinterpret_cast<const long long *>(offsets), out,
-                                 lse, reinterpret_cast<hipStream_t>(stream));
+                                 lse, ws, reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t gvote_decode_workspace_bytes(const gvote_shape *shape, int32_t n_items) {
+  if (check_shape(shape) != GVOTE_OK || n_items < 1) return 0;
+  return decode_ws_bytes(shape, n_items);
 }
 
 gvote_status gvote_attention_overlap(const gvote_shape *shape, const gvote_item *items, int32_t n_items, int32_t S,

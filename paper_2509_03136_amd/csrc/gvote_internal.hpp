@@ -325,8 +325,9 @@ gvote_status launch_count_rows(const gvote_shape *sh, const gvote_item *items, i
                                const uint32_t *rowmask, int repeat, int *counts, hipStream_t st);
 
 size_t overlap_ws_bytes(const gvote_shape *sh, const gvote_item *items, int n_items);
+size_t decode_ws_bytes(const gvote_shape *sh, int n_items);
 gvote_status launch_decode_attention(const gvote_shape *sh, int n_items, const void *q, const void *k_out,
-                                     const void *v_out, const long long *offsets, void *out, float *lse,
+                                     const void *v_out, const long long *offsets, void *out, float *lse, void *ws,
                                      hipStream_t st);
 gvote_status launch_attention_overlap(const gvote_shape *sh, const gvote_item *items, int n_items, int S,
                                       const void *q_real, const uint32_t *rowmask, float *overlap, void *ws,

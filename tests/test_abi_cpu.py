@@ -27,11 +27,12 @@ def test_header_symbols_are_exported(g):
     names = declared_symbols()
     assert {"gvote_fit_gaussian", "gvote_sample_queries", "gvote_score_select", "gvote_union_compact",
             "gvote_workspace_bytes", "gvote_status_string", "gvote_abi_version", "gvote_philox_u32",
-            "gvote_count_rows", "gvote_decode_attention", "gvote_attention_overlap"} <= set(names)
+            "gvote_count_rows", "gvote_decode_attention", "gvote_decode_workspace_bytes", "gvote_attention_overlap",
+            "gvote_union_compact_static", "gvote_debug_set_spin_limit"} <= set(names)
     lib = C.CDLL(g.lib_path())
     for n in names:
         assert hasattr(lib, n), n
-    assert g.abi_version() == 1000
+    assert g.abi_version() == 1001
     for code in range(7):
         assert g.status_string(code)
 
@@ -117,9 +118,17 @@ def test_bad_arguments_are_rejected_before_any_launch(g):
     assert L.gvote_count_rows(C.byref(sh), it, 1, 1, None, 8, 0x100, None) == INVALID
     assert L.gvote_count_rows(C.byref(sh), it, 1, 1, 0x100, 0, 0x200, None) == INVALID
     dec = L.gvote_decode_attention
-    assert dec(C.byref(sh), 1, None, 0x100, 0x200, 0x300, 0x400, None, None) == INVALID
-    assert dec(C.byref(sh), 0, 0x100, 0x100, 0x200, 0x300, 0x400, None, None) == INVALID
-    assert dec(C.byref(_shape(g, head_dim=24)), 1, 0x100, 0x100, 0x200, 0x300, 0x400, None, None) == UNSUP
+    assert dec(C.byref(sh), 1, None, 0x100, 0x200, 0x300, 0x400, None, ws, wsn, None) == INVALID
+    assert dec(C.byref(sh), 0, 0x100, 0x100, 0x200, 0x300, 0x400, None, ws, wsn, None) == INVALID
+    assert dec(C.byref(sh), 1, 0x100, 0x100, 0x200, 0x300, 0x400, None, None, wsn, None) == INVALID
+    assert dec(C.byref(sh), 1, 0x100, 0x100, 0x200, 0x300, 0x400, None, ws, 8, None) == WS
+    assert dec(C.byref(_shape(g, head_dim=24)), 1, 0x100, 0x100, 0x200, 0x300, 0x400, None, ws, wsn, None) == UNSUP
+    assert L.gvote_decode_workspace_bytes(C.byref(sh), 3) > 0 and L.gvote_decode_workspace_bytes(C.byref(sh), 0) == 0
+    # the fit refuses a batch with more row chunks than one launch grid holds, before any launch
+    assert fit(C.byref(sh), _items(g, 32, L=(1 << 31) - 8), 32, 1, 0x100, 0x200, ws, 1 << 40, None) == CAP
+    # the static-scratch variant of stage 4 refuses calls beyond its array
+    assert L.gvote_union_compact_static(C.byref(sh), _items(g, L=1 << 30), 1, 8, 0x100, 0x200, 0x300, 0x400, 0x500, 0x600,
+                                        None, 10, 0x700, None) == CAP
     ovl = L.gvote_attention_overlap
     assert ovl(C.byref(sh), it, 1, 8, None, 0x100, 0x200, ws, wsn, None) == INVALID
     assert ovl(C.byref(sh), it, 1, 8, 0x100, 0x200, 0x300, ws, 8, None) == WS

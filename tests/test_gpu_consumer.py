@@ -43,7 +43,7 @@ def test_decode_attention_over_compressed_cache(g, cfg):
     q_dev = torch.tensor(q).to(pipe.q.dtype).to(DEV)
     out = torch.empty_like(q_dev)
     lse = torch.empty(len(items), wl.n_q_heads, device=DEV, dtype=torch.float32)
-    g.decode_attention(b, q_dev, pipe.k_out, pipe.v_out, pipe.offsets, out, lse)
+    g.decode_attention(b, q_dev, pipe.k_out, pipe.v_out, pipe.offsets, out, pipe.ws, lse)
     torch.cuda.synchronize()
     offs = pipe.offsets.cpu().numpy()
     k_out, v_out = U.f32np(pipe.k_out), U.f32np(pipe.v_out)
