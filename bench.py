@@ -30,6 +30,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 DOMINANT_KERNEL = {"fit": "moments_partial_kernel", "sample": "project_mfma_kernel",
                    "select": "score_hist_kernel", "compact": "gather_kernel"}
+# fp32 storage takes the general kernels (no matrix-core path)
+DOMINANT_KERNEL_F32 = dict(DOMINANT_KERNEL, sample="project_generic_kernel", select="select_row_kernel")
 
 
 def algorithmic_bytes(wl, lengths, rho):
@@ -231,7 +233,7 @@ def main():
     rho = kept / float(tok * wl.n_kv_heads)
     ab = algorithmic_bytes(wl, wl.lengths, rho)
     dom = max(stage_ms, key=stage_ms.get)
-    dom_kernel = DOMINANT_KERNEL[dom]
+    dom_kernel = (DOMINANT_KERNEL if wl.dtype == "bf16" else DOMINANT_KERNEL_F32)[dom]
     if args.traffic_kib is not None:
         traffic = (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
     else:
