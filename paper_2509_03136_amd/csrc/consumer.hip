@@ -4,11 +4,13 @@
 //   decode_attention   one decode query per head against the packed rows of its KV head:
 //                      softmax(q K^T / sqrt(d_k)) V.  The packed rows of a head are split over several
 //                      workgroups (so that few heads still fill the chip); each serves the G query heads of
-//                      the group over its share, so every packed K/V row is read once; rows are contiguous
-//                      in the packed cache: a key row is read by d_k*elem/16 neighbouring lanes, 16 bytes
-//                      each, four row steps in flight; online softmax per lane group, merged across the wave
-//                      by shuffles, across the workgroup through LDS, across the shares by a small merge
-//                      kernel through their log-sum-exp.  Memory-bound (2 * B * d_k * elem bytes per KV head).
+//                      the group over its share, so every packed K/V row is read once (16 bytes per lane,
+//                      a key row by d_k*elem/16 neighbouring lanes); results are merged across the wave by
+//                      shuffles, across the workgroup through LDS, across the shares by a small merge kernel
+//                      through their log-sum-exp.  Memory-bound (2 * B * d_k * elem bytes per KV head).
+//                      bf16 with d_k 64 or 128 and up to 16 heads per KV head: logits of 32-row tiles on the
+//                      matrix cores, one rescale per tile (decode_attention_mfma_kernel); everything else:
+//                      vector units, online softmax per row step (decode_attention_kernel).
 //   attention_overlap  how much of a REAL query's attention falls on the key set a synthetic row chose:
 //                      per (item, query head) the real query's logits over all L keys (kept in the
 //                      workspace), their softmax, and for every sample s the weight inside row (s, h)'s mask.
@@ -138,6 +140,184 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const DecodeArgs 
       a.part[(row * a.n_splits + split) * (dk + 2) + ch] = val;      // ch < dk: numerator; dk: maximum; dk + 1: weight sum
     }
     __syncthreads();
+  }
+}
+
+// ---- bf16, d_k 64 or 128, G <= 16: the logits of 32 packed rows against the group's query heads come from the
+// matrix cores.  Same grid, shares and partial results as decode_attention_kernel.  Per wave and 32-row tile:
+//   K rows (coalesced 16-byte lanes, non-temporal) -> wave-private XOR-swizzled LDS tile -> A operand of
+//   v_mfma_f32_32x32x16_bf16, the B operand holds the query heads as columns (columns >= G are zero), so lane
+//   (col, hf) ends up with the logits of head `col` for 16 of the 32 rows;
+//   the lanes of the G heads take the tile maximum, rescale their running sums once per TILE (not per row) and
+//   leave the 32 x G weights and the G rescale factors in LDS;
+//   the V rows stay in registers as they were loaded (a lane owns 8 channels of every fourth or eighth row):
+//   acc[g][8] = acc[g][8] * corr[g] + sum_rows p[row][g] * v[row][8] on the vector units, the weights coming
+//   from LDS as broadcast reads.
+// The next tile's K and V rows are in flight while the current one is processed.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ int tile_row_of(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }   // C layout of the 32x32 MFMA
+
+template <int DK, int GP>
+__global__ __launch_bounds__(256) void decode_attention_mfma_kernel(const DecodeArgs a) {
+  constexpr int KS = DK / 16, PPR = DK / 8, RPL = 64 / PPR, LOADS = 32 / RPL;
+  constexpr int TILE_BYTES = 32 * DK * 2;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hf = lane >> 5;
+  const int piece = lane % PPR, sub = lane / PPR;
+  const int hh = blockIdx.x, split = blockIdx.y;
+  const int item = hh / a.n_kv_heads, kvh = hh - item * a.n_kv_heads;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const long long lo_h = a.offsets[hh], n_h = a.offsets[hh + 1] - lo_h;
+  const long long lo = lo_h + n_h * split / a.n_splits, hi = lo_h + n_h * (split + 1) / a.n_splits;
+  const char *kb = reinterpret_cast<const char *>(a.k_out);
+  const char *vb = reinterpret_cast<const char *>(a.v_out);
+  __shared__ __align__(16) unsigned char ktile[4][TILE_BYTES];
+  __shared__ __align__(16) float pw[4][32][GP];       // weights of the tile: [row][head]
+  __shared__ __align__(16) float corr_s[4][GP];
+  __shared__ float part[4][GP][DK + 2];               // per wave: acc[d_k], m, l of every head
+
+  // B operand: query head `col` of the group (zero columns beyond G)
+  bf16x8 bq[KS];
+  {
+    const bf16_t *qrow = reinterpret_cast<const bf16_t *>(a.q) + ((size_t)item * a.n_q_heads + kvh * G + (col < G ? col : 0)) * DK + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (col < G) raw = *reinterpret_cast<const uint4 *>(qrow + 16 * ks);
+      bq[ks] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+  float m_run = -INFINITY, l_run = 0.f;      // of head `col`, over this lane's 16 rows of every tile (the two halves share m_run)
+  float acc[GP][8];
+#pragma unroll
+  for (int g = 0; g < GP; ++g)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
+
+  const long long n_rows = hi - lo;
+  const long long n_tiles = (n_rows + 31) >> 5;
+  auto fetch = [&](u32x4_t(&pk)[LOADS], u32x4_t(&pv)[LOADS], long long tile) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+      long long r = lo + tile * 32 + j * RPL + sub;
+      r = r < hi ? r : hi - 1;               // in bounds (hi > lo here); the row's weight is forced to zero
+      pk[j] = load_stream16(kb + (r * DK + piece * 8) * 2);
+      pv[j] = load_stream16(vb + (r * DK + piece * 8) * 2);
+    }
+  };
+  unsigned char *kt = ktile[wave];
+  if (wave < n_tiles) {
+    u32x4_t pk[LOADS], pv[LOADS], vcur[LOADS];
+    fetch(pk, pv, wave);
+    for (long long tile = wave; tile < n_tiles; tile += 4) {
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        const int row = j * RPL + sub;
+        *reinterpret_cast<u32x4_t *>(kt + (row * PPR + (piece ^ (row & (PPR - 1)))) * 16) = pk[j];
+        vcur[j] = pv[j];
+      }
+      {
+        const long long tn = tile + 4 < n_tiles ? tile + 4 : tile;     // (the last tile is fetched again: no conditional load)
+        fetch(pk, pv, tn);
+      }
+      __builtin_amdgcn_wave_barrier();
+      floatx16 c;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) c[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int phys = (2 * ks + hf) ^ (col & (PPR - 1));
+        const bf16x8 ak = *reinterpret_cast<const bf16x8 *>(kt + (col * PPR + phys) * 16);     // row `col` of the tile
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, bq[ks], c, 0, 0, 0);
+      }
+      // softmax bookkeeping of head `col` (all lanes run it; only columns < G are looked at afterwards)
+      const int valid = (int)((hi - lo - tile * 32) < 32 ? (hi - lo - tile * 32) : 32);
+      float mt = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        c[r] = tile_row_of(r, hf) < valid ? c[r] * a.scale : -INFINITY;
+        mt = fmaxf(mt, c[r]);
+      }
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float mn = fmaxf(m_run, mt);                      // finite: row 0 of a tile always exists
+      const float corr = __builtin_amdgcn_exp2f(m_run - mn);   // 2^(-inf) = 0 on the first tile
+      float ls = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(c[r] - mn);
+        ls += pr;
+        if (col < GP) pw[wave][tile_row_of(r, hf)][col] = pr;
+      }
+      l_run = l_run * corr + ls;
+      m_run = mn;
+      if (lane < GP) corr_s[wave][lane] = corr;
+      __builtin_amdgcn_wave_barrier();
+      // output update: this lane's 8 channels of its rows
+      float cg[GP];
+#pragma unroll
+      for (int g4 = 0; g4 < GP; g4 += 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(&corr_s[wave][g4]);
+        cg[g4] = t.x; cg[g4 + 1] = t.y; cg[g4 + 2] = t.z; cg[g4 + 3] = t.w;
+      }
+#pragma unroll
+      for (int g = 0; g < GP; ++g)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[g][i] *= cg[g];
+#pragma unroll
+      for (int j = 0; j < LOADS; ++j) {
+        const int row = j * RPL + sub;
+        float vv[8];
+        vv[0] = __uint_as_float(vcur[j].x << 16); vv[1] = __uint_as_float(vcur[j].x & 0xFFFF0000u);
+        vv[2] = __uint_as_float(vcur[j].y << 16); vv[3] = __uint_as_float(vcur[j].y & 0xFFFF0000u);
+        vv[4] = __uint_as_float(vcur[j].z << 16); vv[5] = __uint_as_float(vcur[j].z & 0xFFFF0000u);
+        vv[6] = __uint_as_float(vcur[j].w << 16); vv[7] = __uint_as_float(vcur[j].w & 0xFFFF0000u);
+#pragma unroll
+        for (int g4 = 0; g4 < GP; g4 += 4) {
+          const float4 t = *reinterpret_cast<const float4 *>(&pw[wave][row][g4]);
+          const float pg[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[g4 + q][i] = fmaf(pg[q], vv[i], acc[g4 + q][i]);
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  // the wave's result: sum the row subsets (lanes with the same piece), the two halves of l
+  l_run += __shfl_xor(l_run, 32, 64);
+#pragma unroll
+  for (int g = 0; g < GP; ++g) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float x = acc[g][i];
+      for (int off = PPR; off < 64; off <<= 1) x += __shfl_xor(x, off, 64);
+      acc[g][i] = x;
+    }
+    if (sub == 0 && g < G) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part[wave][g][piece * 8 + i] = acc[g][i];
+    }
+  }
+  if (lane < G) { part[wave][lane][DK] = m_run; part[wave][lane][DK + 1] = l_run; }
+  __syncthreads();
+  for (int o = threadIdx.x; o < G * (DK + 2); o += 256) {
+    const int g = o / (DK + 2), ch = o - g * (DK + 2);
+    float mn = -INFINITY;
+    for (int w = 0; w < 4; ++w) mn = fmaxf(mn, part[w][g][DK]);
+    float val;
+    if (ch == DK) {
+      val = mn;
+    } else {
+      val = 0.f;
+      for (int w = 0; w < 4; ++w) {
+        const float cw = part[w][g][DK] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(part[w][g][DK] - mn);
+        val = fmaf(part[w][g][ch < DK ? ch : DK + 1], cw, val);
+      }
+    }
+    const size_t row = (size_t)item * a.n_q_heads + kvh * G + g;
+    a.part[(row * a.n_splits + split) * (DK + 2) + ch] = val;      // ch < d_k: numerator; d_k: maximum; d_k + 1: weight sum
   }
 }
 
@@ -291,7 +471,15 @@ gvote_status launch_decode_attention(const gvote_shape *sh, int n_items, const v
     GVOTE_CHECK_LAUNCH();
     hipLaunchKernelGGL(decode_merge_kernel<float>, gridm, dim3(256), 0, st, a);
   } else {
-    hipLaunchKernelGGL(decode_attention_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+    const int G = sh->n_q_heads / sh->n_kv_heads;
+    const bool mfma = (sh->head_dim == 64 || sh->head_dim == 128) && G <= 16;
+    if (!mfma) hipLaunchKernelGGL(decode_attention_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+    else if (sh->head_dim == 128 && G <= 4) hipLaunchKernelGGL((decode_attention_mfma_kernel<128, 4>), grid, dim3(256), 0, st, a);
+    else if (sh->head_dim == 128 && G <= 8) hipLaunchKernelGGL((decode_attention_mfma_kernel<128, 8>), grid, dim3(256), 0, st, a);
+    else if (sh->head_dim == 128) hipLaunchKernelGGL((decode_attention_mfma_kernel<128, 16>), grid, dim3(256), 0, st, a);
+    else if (G <= 4) hipLaunchKernelGGL((decode_attention_mfma_kernel<64, 4>), grid, dim3(256), 0, st, a);
+    else if (G <= 8) hipLaunchKernelGGL((decode_attention_mfma_kernel<64, 8>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((decode_attention_mfma_kernel<64, 16>), grid, dim3(256), 0, st, a);
     GVOTE_CHECK_LAUNCH();
     hipLaunchKernelGGL(decode_merge_kernel<bf16_t>, gridm, dim3(256), 0, st, a);
   }

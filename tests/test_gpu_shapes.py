@@ -80,8 +80,13 @@ def test_head_dim_64_on_the_matrix_core_path(g):
     assert boundary <= 8
 
 
-def test_decode_attention_sixteen_heads_per_kv_head(g):
-    wl = W.scaled(W.config(2), lengths=(900, 130), n_planted=(10, 2), d=1024, n_q_heads=32, n_kv_heads=2, d_k=64, S=4)
+@pytest.mark.parametrize("heads", [(32, 2, 64), (8, 2, 64), (16, 2, 64), (14, 2, 128), (32, 2, 128), (32, 1, 128), (48, 2, 64)],
+                         ids=lambda h: f"Hq{h[0]}_Hkv{h[1]}_dk{h[2]}")
+def test_decode_attention_group_sizes_and_head_dims(g, heads):
+    """Every instantiation of the matrix-core decode kernel (4, 8 or 16 head columns, head_dim 64 and 128) and the
+    vector-unit kernel that serves groups of more than 16 heads."""
+    hq, hkv, dk = heads
+    wl = W.scaled(W.config(2), lengths=(900, 130), n_planted=(10, 2), d=1024, n_q_heads=hq, n_kv_heads=hkv, d_k=dk, S=4)
     items = W.make_items(wl, "cpu")
     b = U.batch_from(g, wl, U.to_device(items, DEV))
     pipe = g.Pipeline(b, wl.S, wl.p, ddof=wl.ddof)
