@@ -178,6 +178,10 @@ struct SampleTable {
   void *h_tilde_out;              // optional user copy, call-indexed
   float *partial;                 // ws: [n_items_batch][ksplits][n_out][SP]
   void *q_out;                    // [n_items_call][S][n_out]
+  // the projection runs once per GROUP of consecutive items that share one W_q (requests through the same
+  // layer): their samples are the columns of one product, W_q is read once per group
+  int n_groups;
+  unsigned char grp_first[kMaxItems], grp_count[kMaxItems];
   SampleItem it[kMaxItems];
 };
 struct SamplePlan {

@@ -84,13 +84,16 @@ __global__ __launch_bounds__(256) void sample_hidden_kernel(const SampleTable ta
   }
 }
 
-// ---- bf16 MFMA projection.  grid (ceil(n_out/256), ksplits, items), 512 threads (8 waves x 32 outputs).
+// ---- bf16 MFMA projection.  grid (ceil(n_out/256), ksplits, item groups), 512 threads (8 waves x 32 outputs).
+// A group is a run of items with the same W_q; its n x S sampled states (contiguous in the workspace) are the
+// columns of one product.
 constexpr int kProjWaves = 8;
 template <int NSB>
 __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const SampleTable tab) {
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t *Bs = reinterpret_cast<bf16_t *>(smem);   // [32*NSB][kslice + 8]
-  const int it = blockIdx.z, ks = blockIdx.y;
+  const int it = tab.grp_first[blockIdx.z], ks = blockIdx.y;
+  const int S_grp = tab.grp_count[blockIdx.z] * tab.S;     // columns of this product
   const int k0 = ks * tab.kslice;
   const int klen = min(tab.kslice, tab.d - k0);
   const int ldb = tab.kslice + 8;
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const Sam
   for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += kProjWaves * 64) {
     const int s = v / vec_per_row, kk = (v % vec_per_row) * 8;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (s < tab.S && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
+    if (s < S_grp && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
     *reinterpret_cast<uint4 *>(Bs + s * ldb + kk) = val;
   }
   __syncthreads();
@@ -192,13 +195,15 @@ __global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const Sam
   }
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   // Rows are outputs o, columns are samples.
-  float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
 #pragma unroll
   for (int sb = 0; sb < NSB; ++sb) {
+    const int v = sb * 32 + col;           // column = (item of the group, sample)
+    const int gi = v / tab.S, sm = v - gi * tab.S;
+    float *part = tab.partial + ((size_t)((it + gi) * tab.ksplits + ks) * tab.n_out) * tab.SPs + sm;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int oo = ob + 8 * (r / 4) + 4 * hf + (r % 4);
-      if (oo < tab.n_out && sb * 32 + col < tab.SPs) part[(size_t)oo * tab.SPs + sb * 32 + col] = acc[sb][r];
+      if (oo < tab.n_out && v < S_grp) part[(size_t)oo * tab.SPs] = acc[sb][r];
     }
   }
 }
@@ -346,9 +351,25 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
       hipLaunchKernelGGL(sample_hidden_kernel<bf16_t>, gs, dim3(256), 0, st, tab);
     GVOTE_CHECK_LAUNCH();
     if (mfma) {
-      const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, nb);
-      const int nsb = plan.SP / 32;
-      const size_t lds = (size_t)plan.SP * (plan.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
+      // groups of consecutive items with one W_q; up to 96 columns per product (three 32-column MFMA blocks: the
+      // staged columns of a 512-channel slice then still fit the LDS)
+      const int per_group = S <= 96 ? 96 / S : 1;
+      int widest = 0;
+      tab.n_groups = 0;
+      for (int i = 0; i < nb; ++i) {
+        const int gl = tab.n_groups - 1;
+        if (gl >= 0 && items[b0 + i].w_q == items[b0 + tab.grp_first[gl]].w_q && tab.grp_count[gl] < per_group) {
+          ++tab.grp_count[gl];
+        } else {
+          tab.grp_first[tab.n_groups] = (unsigned char)i;
+          tab.grp_count[tab.n_groups] = 1;
+          ++tab.n_groups;
+        }
+        if (tab.grp_count[tab.n_groups - 1] > widest) widest = tab.grp_count[tab.n_groups - 1];
+      }
+      const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, tab.n_groups);
+      const int nsb = (widest * S + 31) / 32;
+      const size_t lds = (size_t)(32 * nsb) * (plan.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
       if (lds > kLdsBytesPerCu) return GVOTE_ERR_CAPACITY;       // cannot happen with the slices plan_sample picks
       hipError_t attr = hipSuccess;                               // more than 64 KiB of dynamic LDS must be asked for
       if (nsb == 2 && lds > 65536)

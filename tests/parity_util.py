@@ -157,7 +157,16 @@ def batch_from(g, wl, items, **kw):
 
 
 def to_device(items, dev):
-    out = []
+    """Copies of the items' tensors on `dev`; a tensor that several items share (one layer's weights for a batch of
+    requests) is copied once and stays shared, as a serving engine would hold it."""
+    moved, out = {}, []
     for it in items:
-        out.append({k: (v.to(dev) if isinstance(v, torch.Tensor) else v) for k, v in it.items()})
+        o = {}
+        for k, v in it.items():
+            if isinstance(v, torch.Tensor):
+                if id(v) not in moved:
+                    moved[id(v)] = v.to(dev)
+                v = moved[id(v)]
+            o[k] = v
+        out.append(o)
     return out

@@ -80,6 +80,42 @@ def test_head_dim_64_on_the_matrix_core_path(g):
     assert boundary <= 8
 
 
+@pytest.mark.parametrize("S,n", [(5, 21), (16, 7), (40, 3)])
+def test_requests_that_share_one_layer_are_projected_together(g, S, n):
+    """Items with the same W_q (requests through one layer) go through the projection in groups of up to 96
+    columns: odd sample counts (group columns that straddle the 32-column blocks), a last group that is smaller,
+    and the same queries as when every item is projected alone."""
+    lengths = tuple(64 + 37 * i for i in range(n))
+    wl = W.scaled(W.config(5), lengths=lengths, n_planted=(2,) * n, d=512, n_q_heads=4, n_kv_heads=2, S=S)
+    items = W.make_items(wl, "cpu")
+    assert all(it["w_q"] is items[0]["w_q"] for it in items)
+    refs = [U.oracle_item(wl, it, upto="q") for it in items]
+    dev_items = U.to_device(items, DEV)
+    assert len({it["w_q"].data_ptr() for it in dev_items}) == 1
+    b = U.batch_from(g, wl, dev_items)
+    pipe = g.Pipeline(b, wl.S, wl.p)
+    pipe.mu.copy_(torch.tensor(np.stack([r["mu"] for r in refs])))
+    pipe.var.copy_(torch.tensor(np.stack([r["var"] for r in refs])))
+    pipe.sample()
+    torch.cuda.synchronize()
+    q_grouped = pipe.q.clone()
+    for i, r in enumerate(refs):
+        q = U.f32np(pipe.q[i]).astype(np.float64)
+        qd = np.abs(q - r["q_tilde"])
+        scale = np.sqrt((r["q_tilde"] ** 2).mean())
+        assert np.all(qd <= 2.0 ** -7 * np.abs(r["q_tilde"]) + U.TOL[wl.dtype] * scale), (i, qd.max())
+        assert (qd > 0).mean() < 0.05, (i, (qd > 0).mean())
+    # every item alone (its own copy of the weights): bit-identical queries
+    for i in (0, n - 1):
+        solo = dict(dev_items[i], w_q=dev_items[i]["w_q"].clone())
+        b1 = U.batch_from(g, wl, [solo])
+        p1 = g.Pipeline(b1, wl.S, wl.p)
+        p1.mu.copy_(pipe.mu[i:i + 1]); p1.var.copy_(pipe.var[i:i + 1])
+        p1.sample()
+        torch.cuda.synchronize()
+        assert torch.equal(p1.q[0], q_grouped[i]), i
+
+
 @pytest.mark.parametrize("heads", [(32, 2, 64), (8, 2, 64), (16, 2, 64), (14, 2, 128), (32, 2, 128), (32, 1, 128), (48, 2, 64)],
                          ids=lambda h: f"Hq{h[0]}_Hkv{h[1]}_dk{h[2]}")
 def test_decode_attention_group_sizes_and_head_dims(g, heads):
