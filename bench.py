@@ -227,6 +227,7 @@ def main():
     torch.cuda.synchronize()
     fallback_rows = pipe.fallback_rows() if wl.dtype == "bf16" else None
     fallback_why = pipe.fallback_reasons() if wl.dtype == "bf16" else None
+    refined_rows = pipe.refined_rows() if wl.dtype == "bf16" else None
     tok = sum(wl.lengths)
     budget = pipe.budget.cpu().numpy()
     kept = int(pipe.offsets[-1].item())
@@ -263,6 +264,7 @@ def main():
         "kept_fraction": rho,
         "select_fallback_rows": fallback_rows,
         "select_fallback_by_reason": fallback_why,
+        "select_rows_in_second_window": refined_rows,
         "budget_per_item": [int(x) for x in budget.sum(axis=1)],
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,
@@ -317,7 +319,7 @@ def main():
                        "kept_fraction": int(pipe.offsets[-1].item()) / float(tok * wl.n_kv_heads),
                        "mean_B_step": float(counts.float().mean().item())}
     if args.sweep:
-        values = {"S": [4, 8, 16, 32, 64], "p": [0.5, 0.8, 0.9, 0.95, 0.99]}[args.sweep]
+        values = {"S": [4, 8, 16, 32, 64], "p": [0.5, 0.8, 0.9, 0.95, 0.99, 0.999, 0.9999]}[args.sweep]
         rows = []
         for x in values:
             S, p = (x, wl.p) if args.sweep == "S" else (wl.S, x)
@@ -327,6 +329,7 @@ def main():
             torch.cuda.synchronize()
             fb = pp.fallback_rows()
             rows.append({args.sweep: x, "ms_per_step": ms, "stage_ms": st, "select_fallback_rows": fb,
+                         "select_rows_in_second_window": pp.refined_rows(),
                          "kept_fraction": int(pp.offsets[-1].item()) / float(tok * wl.n_kv_heads)})
             del pp
             torch.cuda.empty_cache()

@@ -146,10 +146,12 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * ws is required (gvote_workspace_bytes): statistics between the passes and the exact selector's logit cache.
  * Diagnostics: when the matrix-core path runs (bf16, head_dim 64 or 128, every L >= 32; TOPP with p < 1, or TOPK) the first int32
  * words of ws hold, after the call and until ws is used again: [0] the number of rows that had to be redone by
- * the exact general selector, and [2..5] that number by reason: the cut lies below the histogram window; a
- * row's candidate lists are full; more candidates around the cut than the resolver holds; a first-pass
- * workgroup gave up waiting for one of its waves (see gvote_debug_set_spin_limit) - such rows are never
- * answered from a partial histogram. */
+ * the exact general selector, and [2..5] that number by reason: the cut lies below the histogram windows (two
+ * windows of 16 logit units each, the first starting up to 4 units above the row maximum); a row's candidate lists
+ * are full; more candidates around the cut than the resolver holds; a first-pass workgroup gave up waiting for
+ * one of its waves (see gvote_debug_set_spin_limit) - such rows are never answered from a partial histogram;
+ * [6] the number of rows whose cut lay below the first window and was found in the second (those
+ * rows cost one more pass over K for their block of 64 rows, not the exact selector). */
 GVOTE_API gvote_status gvote_score_select(const gvote_shape *shape, const gvote_item *items, int32_t n_items,
                                 int32_t S, const void *q, float p, int32_t mode, const int32_t *k_per_row,
                                 uint32_t *rowmask, float *row_max, float *row_sum,

@@ -278,6 +278,10 @@ class Pipeline:
         """(cut below the histogram window, candidate lists full, too many candidates, first pass gave up) row counts."""
         return [int(x) for x in self.ws[8:24].view(torch.int32).tolist()]
 
+    def refined_rows(self) -> int:
+        """Rows of the last select() whose cut lay below their first histogram window and was found in a deeper one."""
+        return int(self.ws[24:28].view(torch.int32).item())
+
     def compact(self):
         union_compact(self.b, self.S, self.rowmask, self.union_mask, self.budget, self.offsets, self.k_out,
                       self.v_out, self.idx_out, self.capacity, self.overflow, self.ws)

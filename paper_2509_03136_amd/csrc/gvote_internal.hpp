@@ -266,6 +266,7 @@ struct FastTable {
   RowInfo *info;            // [rows of the batch]
   int *n_fallback;          // counter of rows redone by the general selector (first word of the workspace)
   int *n_list;              // rows of this batch waiting for the general selector (second word) ...
+  int *n_refine;            // words 8..: rows whose cut lies below their window, per refinement level (device-side early exits)
   int *row_list;            // ... and their batch row indices
   int *cand_cnt;            // [rows][sub_per_row]: entries in each sub-list
   uint2 *cands;             // [rows][sub_per_row][kSubCap]: (raw dot bits, position)

@@ -222,6 +222,9 @@ struct HistCtl {
 constexpr int kTopUnset = -(1 << 24);
 constexpr int kTopGaveUp = -(1 << 25);   // part_top of a (slot, row) whose pass-1 workgroup gave up: find_bin sends the row to the exact selector
 constexpr int kHeadroom = 4 * kBinsPerUnit;
+constexpr int kRefineLevels = 1;        // further 256-bin windows below the first for rows whose cut lies deeper (one more
+                                        // reaches 28..32 units below the maximum: weights of e^-28, beyond what fp32 sums resolve;
+                                        // each level costs two launches that do nothing in the usual case)
 
 template <int DK, bool TWO, bool TOPK>
 __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
@@ -416,6 +419,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
     ctl.rowmax[tid] = ordered_bits(-3.0e38f);
   }
   if (tid == 0) { ctl.pending = 0; ctl.done = 0; ctl.aborted = 0; }
+  if (blockIdx.x == 0 && tid < kRefineLevels + 1) tab.n_refine[tid] = 0;     // (find_bin_kernel counts into it after this kernel)
   __syncthreads();
   if (c.n0 + 32 < tab.NQ)
     hist_fused_body<DK, true, TOPK>(tab, c, I, tiles[wave], hist, &ctl);
@@ -531,6 +535,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
       info->mdot = m;
       info->astar = top - j;
       info->flag = (j == kBins - 1) ? 1 : 0;      // 1: the cut lies below the histogram window
+      if (j == kBins - 1) atomicAdd(tab.n_refine, 1);     // asks for a deeper window (score_refine_kernel)
       info->above = before;
       info->target = target;
     }
@@ -540,13 +545,172 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     if (grow == 0) {
       if (tab.item0 == 0) {
         *tab.n_fallback = 0;
-        tab.n_list[1] = 0; tab.n_list[2] = 0; tab.n_list[3] = 0; tab.n_list[4] = 0;
+        tab.n_list[1] = 0; tab.n_list[2] = 0; tab.n_list[3] = 0; tab.n_list[4] = 0; tab.n_list[5] = 0;
       }
       *tab.n_list = 0;
     }
     const size_t gr = (size_t)(tab.item0 + it) * tab.rows_per_item + r;
     if (tab.row_max) tab.row_max[gr] = m * tab.scale;
     if (tab.row_sum) tab.row_sum[gr] = (float)Z;
+  }
+}
+
+// ------------------------------------------------------------------ deeper windows for rows whose cut lies below the first
+// A row whose cut falls into the last bin of its 256-bin window (flag 1: a far-reaching p, or one dominant key
+// over a long flat tail) gets another window right below the first: the same absolute grid, the window top
+// fixed at the first window's last bin (so nothing slides and no wave waits for another), keys above it
+// ignored - their weight is already in `above`.  Only workgroups with such a row in their block of 64 do
+// anything.  refine_bin_kernel then continues the row's cumulative search in the new bins; a row that is
+// still in a last bin keeps flag 1 and can be refined again.
+template <int DK, bool TWO, bool TOPK>
+__device__ __forceinline__ void hist_fixed_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
+                                                unsigned char *ldstile, uint32_t *hist, const int *top_s) {
+  constexpr int LOADS = Tile<DK>::LOADS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
+            col = lane & 31;
+  Tile<DK> T;
+  T.load_q(tab, c.it, c.kvh, c.n0, lane);
+  const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
+  const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
+  const int last_tile = wave < n_tiles ? wave + kWaves * ((n_tiles - 1 - wave) / kWaves) : n_tiles - 1;
+  const float c1 = tab.c1, c2 = tab.c2;
+  const float ebias = (float)kFixBits - kLog2ePerBin;
+  uint32_t *hrow[2] = {hist + col * (kBins + 1), hist + (32 + col) * (kBins + 1)};
+  // rows that are not being refined keep a harmless window (top 0) and a ceiling no key passes
+  const int top[2] = {top_s[col], top_s[32 + col]};
+  const bool live[2] = {top[0] != kTopUnset, top[1] != kTopUnset};
+  u32x4 pre[LOADS];
+  T.fetch(pre, khead, I.tok_stride, tile_origin(c.t_begin + min(wave, n_tiles - 1) * 32, c.t_end), lane);
+  for (int tile = wave; tile < n_tiles; tile += kWaves) {
+    const int t0 = c.t_begin + tile * 32;
+    const int skip = t0 - tile_origin(t0, c.t_end);
+    floatx16 acc[2];
+    T.stage(pre, ldstile, lane);
+    {
+      const int tn = c.t_begin + min(tile + kWaves, last_tile) * 32;
+      T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
+    }
+    __builtin_amdgcn_wave_barrier();
+    T.template compute<TWO>(acc, ldstile, lane);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      if (nb == 0 || TWO) {
+        const int tp = live[nb] ? top[nb] : 0;
+        const float atop = (float)tp, atail = (float)(tp - (kBins - 1));
+        const float ceil_f = live[nb] ? atop : -INFINITY;       // keys in bins above this are not counted here
+        const float abase = (float)(lds_offset(hrow[nb]) + 4 * tp);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float d = acc[nb][r];
+          const float a = floorf(d * c1);
+          const float af = fminf(fmaxf(a, atail), atop);
+          uint32_t u = 1u;
+          if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
+          if (!(a <= ceil_f) || key_of(r, hf) < skip) u = 0u;
+          lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
+          if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
+}
+
+template <int DK, bool TOPK>
+__global__ __launch_bounds__(kThreads) void score_refine_kernel(const FastTable tab, int level) {
+  __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
+  __shared__ uint32_t hist[64 * (kBins + 1)];
+  __shared__ int top_s[64];
+  __shared__ int any_s;
+  if (tab.n_refine[level] == 0) return;    // nobody asked (the usual case): one scalar load per workgroup
+  int wg_id = blockIdx.x;
+  if (!xcd_order(tab, wg_id)) return;
+  const WgCoord c = decode_wg(tab, wg_id);
+  const FastItem I = tab.it[c.it];
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (tid == 0) any_s = 0;
+  __syncthreads();
+  if (tid < 64) {
+    int t = kTopUnset;
+    const int n = c.n0 + tid;
+    if (n < tab.NQ) {
+      const int s = n / tab.G, g = n % tab.G;
+      const RowInfo &ri = tab.info[c.it * tab.rows_per_item + s * tab.Hq + c.kvh * tab.G + g];
+      if (ri.flag == 1) { t = ri.astar; any_s = 1; }      // astar of a flag-1 row = its window's last bin
+    }
+    top_s[tid] = t;
+  }
+  for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0u;
+  __syncthreads();
+  if (any_s == 0) return;                  // (uniform: read after the barrier)
+  if (c.n0 + 32 < tab.NQ)
+    hist_fixed_body<DK, true, TOPK>(tab, c, I, tiles[wave], hist, top_s);
+  else
+    hist_fixed_body<DK, false, TOPK>(tab, c, I, tiles[wave], hist, top_s);
+  __syncthreads();
+  const int rows = min(64, tab.NQ - c.n0);
+  uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
+  for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
+}
+
+// one wave per row: continue the cumulative search of a flag-1 row in its refined window
+__global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastTable tab, int n_rows, int level) {
+  if (tab.n_refine[level] == 0) return;
+  const int lane = threadIdx.x & 63;
+  const int grow = blockIdx.x * kFindWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (grow >= n_rows) return;
+  RowInfo *info = tab.info + grow;
+  if (info->flag != 1) return;
+  const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
+  const int s = r / tab.Hq, h = r - s * tab.Hq;
+  const int kvh = h / tab.G, g = h - kvh * tab.G;
+  const int n = s * tab.G + g;
+  const FastItem I = tab.it[it];
+  const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
+  const bool topk = tab.mode == GVOTE_SELECT_TOPK;
+  const int top = info->astar;
+  const double mref = (double)info->mdot * (double)tab.c2;
+  constexpr int BPL = kBins / 64;
+  double mine[BPL];
+#pragma unroll
+  for (int i = 0; i < BPL; ++i) {
+    const int j = lane + 64 * i;
+    unsigned long long a = 0ull;
+    for (int ch = 0; ch < I.n_chunks; ++ch) a += tab.part_hist[((slot0 + ch) * tab.NQ + n) * kBins + j];
+    mine[i] = topk ? (double)a
+                   : (a ? ldexp((double)a, -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0);
+  }
+  double cum[BPL], base = info->above;
+#pragma unroll
+  for (int i = 0; i < BPL; ++i) {
+    double x = mine[i];
+    for (int off = 1; off < 64; off <<= 1) {
+      const double y = __shfl_up(x, off, 64);
+      if (lane >= off) x += y;
+    }
+    cum[i] = base + x;
+    base += __shfl(x, 63, 64);
+  }
+  const double target = info->target;
+  // (fixed-point truncation can leave the refined bins a hair short of the first window's last bin: a target
+  // that no bin reaches stays with the last bin)
+  const bool reached = base >= target;
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int i = 0; i < BPL; ++i) {
+    const int j = lane + 64 * i;
+    const double before = cum[i] - mine[i];
+    const bool here = reached ? (before < target && cum[i] >= target) : (j == kBins - 1);
+    if (here) {
+      info->astar = top - j;
+      info->above = before;
+      if (j != kBins - 1) {
+        info->flag = 0;
+        atomicAdd(tab.n_list + 5, 1);                 // diagnostic: rows settled by a deeper window
+      } else {
+        atomicAdd(tab.n_refine + level + 1, 1);       // still below: next level, or the exact selector
+      }
+    }
   }
 }
 
@@ -973,6 +1137,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
     tab.rowmask = rowmask; tab.row_max = row_max; tab.row_sum = row_sum;
     tab.n_fallback = reinterpret_cast<int *>(wsb);
     tab.n_list = reinterpret_cast<int *>(wsb) + 1;
+    tab.n_refine = reinterpret_cast<int *>(wsb) + 8;
     tab.row_list = reinterpret_cast<int *>(wsb + pl.off_list);
     tab.ovf_cnt = reinterpret_cast<int *>(wsb + pl.off_ovfc);
     tab.ovf = reinterpret_cast<uint2 *>(wsb + pl.off_ovf);
@@ -1010,6 +1175,13 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
+      for (int lvl = 0; lvl < kRefineLevels; ++lvl) {
+        if (topk) hipLaunchKernelGGL((score_refine_kernel<128, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
+        else hipLaunchKernelGGL((score_refine_kernel<128, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
+        GVOTE_CHECK_LAUNCH();
+        hipLaunchKernelGGL(refine_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
+        GVOTE_CHECK_LAUNCH();
+      }
       hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
     } else {
       if (topk) hipLaunchKernelGGL((score_hist_kernel<64, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
@@ -1017,6 +1189,13 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
       GVOTE_CHECK_LAUNCH();
       hipLaunchKernelGGL(find_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
       GVOTE_CHECK_LAUNCH();
+      for (int lvl = 0; lvl < kRefineLevels; ++lvl) {
+        if (topk) hipLaunchKernelGGL((score_refine_kernel<64, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
+        else hipLaunchKernelGGL((score_refine_kernel<64, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
+        GVOTE_CHECK_LAUNCH();
+        hipLaunchKernelGGL(refine_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
+        GVOTE_CHECK_LAUNCH();
+      }
       hipLaunchKernelGGL(score_emit_kernel<64>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();

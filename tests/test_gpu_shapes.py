@@ -145,6 +145,65 @@ def test_decode_attention_group_sizes_and_head_dims(g, heads):
         assert np.all(np.abs(lse[i].cpu().numpy() - want_lse) <= 2e-3 * (1 + np.abs(want_lse)))
 
 
+def test_cut_below_the_first_window_is_found_in_a_deeper_one(g):
+    """A far-reaching p, and one dominant key over a long flat tail: the cut lies more than 12 logit units below
+    the row maximum, outside the first 256-bin window.  Such rows get a second (third) window on the same grid
+    instead of the exact selector; the masks still match the oracle's on the same stored queries."""
+    wl = W.scaled(W.config(2), lengths=(6000, 1300), n_planted=(60, 10), S=8)
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it) for it in items]
+    stol = U.STAGE_TOL["bf16"]
+
+    def run(its, q, p):
+        b = U.batch_from(g, wl, U.to_device(its, DEV))
+        pipe = g.Pipeline(b, wl.S, p)
+        pipe.q.copy_(torch.tensor(np.stack(q)).to(pipe.q.dtype))
+        pipe.select()
+        torch.cuda.synchronize()
+        out, off = [], 0
+        for i, it in enumerate(its):
+            out.append(U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, it["L"]).reshape(wl.S, wl.n_q_heads, it["L"]))
+            off += pipe.mask_words[i]
+        return out, pipe.fallback_rows(), pipe.refined_rows(), pipe.fallback_reasons()
+
+    most = 0
+    for p in (0.999, 0.9999, 0.99999, 0.999999):
+        masks, n_fb, n_ref, why = run(items, [r["q_tilde"] for r in refs], p)
+        nb = deep = 0
+        for gm, r in zip(masks, refs):
+            nb += U.check_rowmask_strict(gm, r["logits"], U.p32(p), min(stol, (1 - U.p32(p)) / 4),
+                                         vtol=max((1 - U.p32(p)) / 2, 1e-6))
+            lg = r["logits"]
+            cut = np.where(r["rowmask"] if p == wl.p else np.stack([[O.top_p_select(lg[s, h], U.p32(p)) for h in range(wl.n_q_heads)]
+                                                                      for s in range(wl.S)]), lg, np.inf).min(-1)
+            deep += int((lg.max(-1) - cut > 16.0).sum())       # the first window ends 12 .. 16 units below the maximum
+        say(f"  p {p}: rows settled in a deeper window {n_ref} (oracle cuts deeper than 16 units: {deep}), "
+            f"redone exactly {n_fb} {why}, boundary keys {nb}")
+        assert n_ref >= deep and why[0] == 0
+        most = max(most, n_ref)
+    assert most > 0
+    # one dominant key 13 units above a long, nearly flat rest: the key alone holds 94.5 % of the mass, p = 0.95
+    # needs hundreds of tail keys, the cut lies 12.7 units below the maximum
+    wl = W.scaled(W.config(2), lengths=(30000,), n_planted=(60,), S=2)
+    it = W.make_items(wl, "cpu")[0]
+    ref = U.oracle_item(wl, it, upto="q")
+    gen = torch.Generator().manual_seed(5)
+    kf = (0.42 * torch.randn(it["k"].shape, generator=gen)).to(it["k"].dtype)
+    qn = ref["q_tilde"][0].reshape(wl.n_kv_heads, wl.group, wl.d_k)[:, 0]           # one query direction per KV head
+    qn = qn / np.linalg.norm(qn, axis=-1, keepdims=True)
+    q1 = np.repeat(np.repeat(qn[:, None], wl.group, axis=1).reshape(1, wl.n_q_heads, wl.d_k), wl.S, axis=0) * 8.0
+    q1 = U.f32np(torch.tensor(q1).to(torch.bfloat16)).astype(np.float64)
+    kf[77] = torch.tensor(qn * (13.2 * np.sqrt(wl.d_k) / 8.0), dtype=torch.float32).to(kf.dtype)
+    sink = dict(it, k=kf)
+    lg = O.scores(q1, U.f32np(kf))
+    masks, n_fb, n_ref, why = run([sink], [q1], 0.95)
+    depth = np.array([lg[s, h].max() - lg[s, h][masks[0][s, h]].min() for s in range(wl.S) for h in range(wl.n_q_heads)])
+    nb = U.check_rowmask_strict(masks[0], lg, U.p32(0.95), stol)
+    say(f"  dominant key: rows settled in a deeper window {n_ref}, redone exactly {n_fb} {why}, boundary keys {nb}, "
+        f"mean row size {masks[0].sum(-1).mean():.0f}, cut {depth.min():.2f} .. {depth.max():.2f} units below the maximum")
+    assert depth.min() > 12.2 and why[0] == 0
+
+
 def test_first_pass_give_up_path_sends_rows_to_the_exact_selector(g):
     """With a spin limit of 0 a first-pass wave that finishes before its workgroup gives up at once: the
     workgroup publishes no histogram, its rows are flagged and the exact selector redoes them.  The masks
