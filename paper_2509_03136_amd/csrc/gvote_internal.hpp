@@ -230,8 +230,9 @@ constexpr int kOvfCap = 256;          // entries of a row's shared overflow list
 struct RowInfo {
   float mdot;       // row maximum of the raw dot product
   int astar;        // absolute bin index floor(dot * c1) in which the cut falls
-  int flag;         // odd: redo this row with the general selector (1 window, 3 lists full, 5 too many candidates, 7 pass 1 gave up); 2: second resolve tier
-  int pad;
+  int flag;         // odd: redo this row with the general selector (1 window, 3 lists full, 5 too many candidates, 7 pass 1 gave up); 2: second resolve tier;
+                    // 4 (between find_bin and refine_bin only): too many keys in the cut bin, look inside it with finer bins
+  int shift;        // astar counts bins of 2^-shift standard bins (0; 8 once the cut bin has been looked into)
   double above;     // weight of all keys in bins above astar (relative to exp(-max)); their number in TOPK mode
   double target;    // p * Z; k in TOPK mode
 };

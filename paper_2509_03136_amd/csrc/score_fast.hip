@@ -222,6 +222,8 @@ struct HistCtl {
 constexpr int kTopUnset = -(1 << 24);
 constexpr int kTopGaveUp = -(1 << 25);   // part_top of a (slot, row) whose pass-1 workgroup gave up: find_bin sends the row to the exact selector
 constexpr int kHeadroom = 4 * kBinsPerUnit;
+constexpr int kFineShift = 8, kFineBins = 1 << kFineShift;   // bins inside a cut bin: 1/4096 of a logit unit
+constexpr int kFineTrigger = 3500;     // keys in a cut bin beyond which it is looked into (the resolver holds kCandCap = 4096)
 constexpr int kRefineLevels = 1;        // further 256-bin windows below the first for rows whose cut lies deeper (one more
                                         // reaches 28..32 units below the maximum: weights of e^-28, beyond what fp32 sums resolve;
                                         // each level costs two launches that do nothing in the usual case)
@@ -463,6 +465,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     if (lane == 0) {
       info->mdot = m;
       info->astar = 0x7FFFFFFF;   // pass 2 ignores the row
+      info->shift = 0;
       info->flag = 7;
       info->above = 0.0;
       info->target = 0.0;
@@ -534,8 +537,23 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     if (!gave_up && before < target && cum[i] >= target) {
       info->mdot = m;
       info->astar = top - j;
-      info->flag = (j == kBins - 1) ? 1 : 0;      // 1: the cut lies below the histogram window
-      if (j == kBins - 1) atomicAdd(tab.n_refine, 1);     // asks for a deeper window (score_refine_kernel)
+      info->shift = 0;
+      int flag = (j == kBins - 1) ? 1 : 0;      // 1: the cut lies below the histogram window
+      // keys in the cut bin: every key adds between 0.94 and 1 times 2^kFixBits to its bin (weights are relative to
+      // the bin's own upper edge), so the fixed-point sum also counts them.  More than the resolver can hold
+      // (flat attention over a long context): look inside the bin with 256 finer bins first.
+      // Pass 2 collects the bin's keys in n_sub = I.n_chunks * emit_split * 2 * kWaves private lists of kSubCap = 16
+      // entries per row plus kOvfCap = 256 shared ones.  With an average fill f the lists spill about
+      // n_sub * E[(Poisson(f) - 16)+] entries: 3.0 per list at f = 18, 1.0 at 15, 0.3 at 13, 0.06 at 11 - the fills
+      // below keep the spill under 200.  (A second pass over K for a block costs less than one row in the exact
+      // selector, but far more than a bin that fits.)
+      const double in_bin = (topk ? mine[i] : (double)acc[i] * (1.0 / (double)(1 << kFixBits))) * 1.07;
+      const int n_sub = I.n_chunks * tab.emit_split * 2 * kWaves;
+      const double fill = n_sub <= 64 ? 18.0 : (n_sub <= 160 ? 15.0 : (n_sub <= 512 ? 13.0 : 11.0));
+      const double room = fmin((double)kFineTrigger, fill * (double)n_sub);
+      if (flag == 0 && in_bin > room) flag = 4;
+      info->flag = flag;
+      if (flag != 0) atomicAdd(tab.n_refine, 1);     // asks for a second histogram (score_refine_kernel)
       info->above = before;
       info->target = target;
     }
@@ -564,7 +582,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
 // still in a last bin keeps flag 1 and can be refined again.
 template <int DK, bool TWO, bool TOPK>
 __device__ __forceinline__ void hist_fixed_body(const FastTable &tab, const WgCoord &c, const FastItem &I,
-                                                unsigned char *ldstile, uint32_t *hist, const int *top_s) {
+                                                unsigned char *ldstile, uint32_t *hist, const int *top_s, const int *shift_s) {
   constexpr int LOADS = Tile<DK>::LOADS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5,
             col = lane & 31;
@@ -573,11 +591,14 @@ __device__ __forceinline__ void hist_fixed_body(const FastTable &tab, const WgCo
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
   const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
   const int last_tile = wave < n_tiles ? wave + kWaves * ((n_tiles - 1 - wave) / kWaves) : n_tiles - 1;
-  const float c1 = tab.c1, c2 = tab.c2;
-  const float ebias = (float)kFixBits - kLog2ePerBin;
+  const float c2 = tab.c2;
   uint32_t *hrow[2] = {hist + col * (kBins + 1), hist + (32 + col) * (kBins + 1)};
   // rows that are not being refined keep a harmless window (top 0) and a ceiling no key passes
   const int top[2] = {top_s[col], top_s[32 + col]};
+  // a row's bins are 2^-shift standard bins wide (scaling by a power of two is exact: floor(d c1 2^shift) is the
+  // same number pass 2 compares against)
+  const float c1r[2] = {ldexpf(tab.c1, shift_s[col]), ldexpf(tab.c1, shift_s[32 + col])};
+  const float kr[2] = {ldexpf(kLog2ePerBin, -shift_s[col]), ldexpf(kLog2ePerBin, -shift_s[32 + col])};
   const bool live[2] = {top[0] != kTopUnset, top[1] != kTopUnset};
   u32x4 pre[LOADS];
   T.fetch(pre, khead, I.tok_stride, tile_origin(c.t_begin + min(wave, n_tiles - 1) * 32, c.t_end), lane);
@@ -600,13 +621,14 @@ __device__ __forceinline__ void hist_fixed_body(const FastTable &tab, const WgCo
         const float atop = (float)tp, atail = (float)(tp - (kBins - 1));
         const float ceil_f = live[nb] ? atop : -INFINITY;       // keys in bins above this are not counted here
         const float abase = (float)(lds_offset(hrow[nb]) + 4 * tp);
+        const float c1 = c1r[nb], nk = -kr[nb], ebias = (float)kFixBits - kr[nb];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float d = acc[nb][r];
           const float a = floorf(d * c1);
           const float af = fminf(fmaxf(a, atail), atop);
           uint32_t u = 1u;
-          if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
+          if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, nk, ebias)));
           if (!(a <= ceil_f) || key_of(r, hf) < skip) u = 0u;
           lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
           if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
@@ -620,7 +642,7 @@ template <int DK, bool TOPK>
 __global__ __launch_bounds__(kThreads) void score_refine_kernel(const FastTable tab, int level) {
   __shared__ __align__(16) unsigned char tiles[kWaves][Tile<DK>::BYTES];
   __shared__ uint32_t hist[64 * (kBins + 1)];
-  __shared__ int top_s[64];
+  __shared__ int top_s[64], shift_s[64];
   __shared__ int any_s;
   if (tab.n_refine[level] == 0) return;    // nobody asked (the usual case): one scalar load per workgroup
   int wg_id = blockIdx.x;
@@ -631,22 +653,24 @@ __global__ __launch_bounds__(kThreads) void score_refine_kernel(const FastTable 
   if (tid == 0) any_s = 0;
   __syncthreads();
   if (tid < 64) {
-    int t = kTopUnset;
+    int t = kTopUnset, sh = 0;
     const int n = c.n0 + tid;
     if (n < tab.NQ) {
       const int s = n / tab.G, g = n % tab.G;
       const RowInfo &ri = tab.info[c.it * tab.rows_per_item + s * tab.Hq + c.kvh * tab.G + g];
       if (ri.flag == 1) { t = ri.astar; any_s = 1; }      // astar of a flag-1 row = its window's last bin
+      if (ri.flag == 4) { t = (ri.astar + 1) * kFineBins - 1; sh = kFineShift; any_s = 1; }   // the finest bin under the cut bin's upper edge
     }
     top_s[tid] = t;
+    shift_s[tid] = sh;
   }
   for (int i = tid; i < 64 * (kBins + 1); i += kThreads) hist[i] = 0u;
   __syncthreads();
   if (any_s == 0) return;                  // (uniform: read after the barrier)
   if (c.n0 + 32 < tab.NQ)
-    hist_fixed_body<DK, true, TOPK>(tab, c, I, tiles[wave], hist, top_s);
+    hist_fixed_body<DK, true, TOPK>(tab, c, I, tiles[wave], hist, top_s, shift_s);
   else
-    hist_fixed_body<DK, false, TOPK>(tab, c, I, tiles[wave], hist, top_s);
+    hist_fixed_body<DK, false, TOPK>(tab, c, I, tiles[wave], hist, top_s, shift_s);
   __syncthreads();
   const int rows = min(64, tab.NQ - c.n0);
   uint32_t *out = tab.part_hist + ((size_t)c.slot * tab.NQ + c.n0) * kBins;
@@ -660,7 +684,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
   const int grow = blockIdx.x * kFindWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
-  if (info->flag != 1) return;
+  if (info->flag != 1 && info->flag != 4) return;
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const int s = r / tab.Hq, h = r - s * tab.Hq;
   const int kvh = h / tab.G, g = h - kvh * tab.G;
@@ -668,7 +692,10 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
   const FastItem I = tab.it[it];
   const size_t slot0 = (size_t)(I.part0 + kvh * I.n_chunks);
   const bool topk = tab.mode == GVOTE_SELECT_TOPK;
-  const int top = info->astar;
+  const bool fine = info->flag == 4;
+  const int sh = fine ? kFineShift : 0;
+  const int top = fine ? (info->astar + 1) * kFineBins - 1 : info->astar;
+  const double kr = ldexp((double)kLog2ePerBin, -sh);
   const double mref = (double)info->mdot * (double)tab.c2;
   constexpr int BPL = kBins / 64;
   double mine[BPL];
@@ -678,7 +705,7 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
     unsigned long long a = 0ull;
     for (int ch = 0; ch < I.n_chunks; ++ch) a += tab.part_hist[((slot0 + ch) * tab.NQ + n) * kBins + j];
     mine[i] = topk ? (double)a
-                   : (a ? ldexp((double)a, -kFixBits) * exp2((double)(top - j + 1) * (double)kLog2ePerBin - mref) : 0.0);
+                   : (a ? ldexp((double)a, -kFixBits) * exp2((double)(top - j + 1) * kr - mref) : 0.0);
   }
   double cum[BPL], base = info->above;
 #pragma unroll
@@ -703,8 +730,11 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
     const bool here = reached ? (before < target && cum[i] >= target) : (j == kBins - 1);
     if (here) {
       info->astar = top - j;
+      info->shift = sh;
       info->above = before;
-      if (j != kBins - 1) {
+      // (inside a cut bin the last fine bin also collects every key below the bin, which cannot matter: the bin as a
+      // whole reaches the target, so a crossing found there is the true one and `before` is exact)
+      if (j != kBins - 1 || fine) {
         info->flag = 0;
         atomicAdd(tab.n_list + 5, 1);                 // diagnostic: rows settled by a deeper window
       } else {
@@ -721,7 +751,8 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
 constexpr int kMaxChunkWords = 8 * kRoundKeys / 32;     // mask words per row of the largest pass-2 piece (256)
 struct EmitShared {
   uint32_t mwords[64][kMaxChunkWords + 1];
-  int astar[64];
+  int astar[64];    // the cut bin on the standard grid (the tile test), 0x7FFFFFFF for rows pass 2 leaves alone
+  float lo[64], hi[64];   // d * c1 in [lo, hi): the key lies in the row's cut bin; >= hi: above it (the bin may be a fine one)
   int row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
 };
 
@@ -736,7 +767,7 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   T.load_q(tab, c.it, c.kvh, c.n0, lane);
   const bf16_t *khead = reinterpret_cast<const bf16_t *>(I.k) + (long long)c.kvh * I.head_stride;
   const float c1 = tab.c1;
-  const int astar[2] = {E->astar[col], E->astar[32 + col]};
+  const float lo_r[2] = {E->lo[col], E->lo[32 + col]}, hi_r[2] = {E->hi[col], E->hi[32 + col]};
   const int grow[2] = {row_base + E->row[col], row_base + E->row[32 + col]};   // only used for rows that exist
   const int n_tiles = (c.t_end - c.t_begin + 31) >> 5;
   const int nk = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;   // tiles of this wave (<= 32)
@@ -795,7 +826,7 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       if (nb == 0 || TWO) {
-        const float lo = (float)astar[nb], hi = (float)astar[nb] + 1.0f;
+        const float lo = lo_r[nb], hi = hi_r[nb];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float x = acc[nb][r] * c1;
@@ -896,12 +927,21 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
   if (tid < 64) {
     const int n = c.n0 + tid;
     int a = 0x7FFFFFFF, r = -1;
+    float lo = 3.0e38f, hi = 3.0e38f;
     if (n < tab.NQ) {
       const int s = n / tab.G, g = n % tab.G;
       r = s * tab.Hq + c.kvh * tab.G + g;
-      a = tab.info[row_base + r].astar;
+      const RowInfo &ri = tab.info[row_base + r];
+      a = ri.astar;
+      if (a != 0x7FFFFFFF) {
+        lo = ldexpf((float)a, -ri.shift);            // exact: |a| < 2^24
+        hi = ldexpf((float)a + 1.0f, -ri.shift);
+        a >>= ri.shift;                               // (arithmetic shift = floor: the standard bin that holds the fine one)
+      }
     }
     E.astar[tid] = a;
+    E.lo[tid] = lo;
+    E.hi[tid] = hi;
     E.row[tid] = r;
   }
   for (int i = tid; i < 64 * (kMaxChunkWords + 1); i += kThreads) (&E.mwords[0][0])[i] = 0u;
@@ -951,7 +991,7 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const FastItem I = tab.it[it];
   // fixed-point scale: weights relative to the upper edge of the cut bin, 2^kFixBits each at most
-  const double edge = (double)(info->astar + 1) * (double)kLog2ePerBin;       // log2 units
+  const double edge = ldexp((double)(info->astar + 1) * (double)kLog2ePerBin, -info->shift);       // log2 units
   const float efix = (float)((double)kFixBits - edge);
   const bool topk = tab.mode == GVOTE_SELECT_TOPK;
   const double unit = topk ? 1.0 : exp2((double)info->mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);

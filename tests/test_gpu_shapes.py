@@ -204,6 +204,57 @@ def test_cut_below_the_first_window_is_found_in_a_deeper_one(g):
     assert depth.min() > 12.2 and why[0] == 0
 
 
+def test_crowded_cut_bin_is_looked_into_with_finer_bins(g):
+    """Nearly flat attention over a long context: thousands of keys share the 1/16-logit bin of the cut, more than the
+    candidate resolver holds.  The bin is then split into 256 finer ones (a second histogram pass) instead of handing
+    the row to the exact selector.  Both selection rules."""
+    wl = W.scaled(W.config(2), lengths=(30000, 9000), n_planted=(60, 20), S=2)
+    items = W.make_items(wl, "cpu")
+    gen = torch.Generator().manual_seed(9)
+    stol = U.STAGE_TOL["bf16"]
+    flat, qs, lgs = [], [], []
+    for it in items:
+        ref = U.oracle_item(wl, it, upto="q")
+        kf = (0.03 * torch.randn(it["k"].shape, generator=gen)).to(it["k"].dtype)
+        flat.append(dict(it, k=kf))
+        qs.append(ref["q_tilde"])
+        lgs.append(O.scores(ref["q_tilde"], U.f32np(kf)))
+    b = U.batch_from(g, wl, U.to_device(flat, DEV))
+    pipe = g.Pipeline(b, wl.S, 0.9)
+    pipe.q.copy_(torch.tensor(np.stack(qs)).to(pipe.q.dtype))
+    pipe.select()
+    torch.cuda.synchronize()
+    n_fb, n_ref, why = pipe.fallback_rows(), pipe.refined_rows(), pipe.fallback_reasons()
+    off = nb = 0
+    for i, it in enumerate(flat):
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, it["L"]).reshape(wl.S, wl.n_q_heads, it["L"])
+        off += pipe.mask_words[i]
+        nb += U.check_rowmask_strict(gm, lgs[i], U.p32(0.9), stol)
+    in_bin = int(((lgs[0][0, 0] * 16 >= np.floor(np.sort(lgs[0][0, 0])[3000] * 16)) & (lgs[0][0, 0] * 16 < np.floor(np.sort(lgs[0][0, 0])[3000] * 16) + 1)).sum())
+    say(f"  top-p: rows settled by a second histogram {n_ref}, redone exactly {n_fb} {why}, boundary keys {nb}; "
+        f"about {in_bin} of {flat[0]['L']} keys share a 1/16-logit bin")
+    assert n_ref > 0 and n_fb == 0
+    # the same rows by count (Alg. 1's TopK): k in the crowded region
+    R = wl.S * wl.n_q_heads
+    ks = torch.tensor(np.tile((np.arange(R) * 131 % 7000 + 1500).astype(np.int32), len(flat)), device=DEV)
+    g.score_select(b, wl.S, pipe.q, 0.5, pipe.rowmask, mode=g.SELECT_TOPK, k_per_row=ks, ws=pipe.ws)
+    torch.cuda.synchronize()
+    n_fb, n_ref = pipe.fallback_rows(), pipe.refined_rows()
+    off = 0
+    kk = ks.cpu().numpy().reshape(len(flat), R)
+    for i, it in enumerate(flat):
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, it["L"]).reshape(R, it["L"])
+        off += pipe.mask_words[i]
+        lg = lgs[i].reshape(R, -1)
+        for r in range(R):
+            k = min(int(kk[i, r]), it["L"])
+            assert gm[r].sum() == k, (i, r, gm[r].sum(), k)
+            # the k-th largest logit separates the sets up to the score tolerance
+            assert lg[r][gm[r]].min() >= (lg[r][~gm[r]].max() if k < it["L"] else -np.inf) - U.logit_slack(lg[r], stol)
+    say(f"  top-k: rows settled by a second histogram {n_ref}, redone exactly {n_fb}")
+    assert n_ref > 0 and n_fb == 0
+
+
 def test_first_pass_give_up_path_sends_rows_to_the_exact_selector(g):
     """With a spin limit of 0 a first-pass wave that finishes before its workgroup gives up at once: the
     workgroup publishes no histogram, its rows are flagged and the exact selector redoes them.  The masks
