@@ -204,6 +204,31 @@ def test_cut_below_the_first_window_is_found_in_a_deeper_one(g):
     assert depth.min() > 12.2 and why[0] == 0
 
 
+@pytest.mark.parametrize("shape", [dict(S=16), dict(S=24), dict(S=20, d_k=64, n_q_heads=16, n_kv_heads=4, d=1024)],
+                         ids=["64_rows", "96_rows", "head_dim_64"])
+def test_second_histogram_on_full_and_partial_row_blocks(g, shape):
+    """The second histogram pass on blocks of 64 rows (both 32-row halves in use), on a KV group with one full and
+    one half-full block, and with head_dim 64; p = 0.9999 sends many rows below their first window."""
+    wl = W.scaled(W.config(2), lengths=(2500, 700), n_planted=(30, 8), **shape)
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it) for it in items]
+    p = 0.9999
+    b = U.batch_from(g, wl, U.to_device(items, DEV))
+    pipe = g.Pipeline(b, wl.S, p)
+    pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+    pipe.select()
+    torch.cuda.synchronize()
+    n_fb, n_ref, why = pipe.fallback_rows(), pipe.refined_rows(), pipe.fallback_reasons()
+    off = nb = 0
+    for i, (it, r) in enumerate(zip(items, refs)):
+        gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, it["L"]).reshape(wl.S, wl.n_q_heads, it["L"])
+        off += pipe.mask_words[i]
+        nb += U.check_rowmask_strict(gm, r["logits"], U.p32(p), min(U.STAGE_TOL["bf16"], (1 - U.p32(p)) / 4),
+                                     vtol=max((1 - U.p32(p)) / 2, 1e-6))
+    say(f"  rows settled by a second histogram {n_ref} of {len(items) * wl.S * wl.n_q_heads}, redone exactly {n_fb} {why}, boundary keys {nb}")
+    assert n_ref > 0 and why[0] == 0
+
+
 def test_crowded_cut_bin_is_looked_into_with_finer_bins(g):
     """Nearly flat attention over a long context: thousands of keys share the 1/16-logit bin of the cut, more than the
     candidate resolver holds.  The bin is then split into 256 finer ones (a second histogram pass) instead of handing
