@@ -11,6 +11,10 @@
 //                per (32-key tile, row) maxima.
 //   find_bin     per row: merge the chunks, Z, target p*Z, walk the bins from the top: the bin
 //                a* where the cumulative weight crosses the target, and the weight above it.
+//   score_refine a second histogram for the rows the first cannot settle (does nothing otherwise): a
+//   refine_bin   cut below the window gets a window right below it; a cut bin with more keys than
+//                pass 2 can list is split into 256 bins of 1/4096 logit.  Same grid arithmetic, the
+//                window top is fixed, keys above it are ignored.
 //   score_emit   pass 2 over K, only over tiles whose maxima reach some row's cut bin: keys in bins
 //                above a* are selected outright (bit masks, transposed in LDS so every row writes
 //                whole 128-byte runs); keys inside bin a* are appended (raw dot, position) to the
@@ -19,8 +23,8 @@
 //                descending, position ascending), so ties go to the lower position - a pairwise
 //                "weight ahead of me" test for up to 64 candidates, a radix search beyond - and OR
 //                of the chosen bits into the mask.
-// Rows whose cut falls below the histogram window, or whose candidate lists overflow, are queued
-// and redone by the exact general selector (select_row_kernel).
+// Rows whose cut falls below the second window as well, or whose candidate lists still overflow, are
+// queued and redone by the exact general selector (select_row_kernel).
 //
 // A workgroup is 8 waves; a wave owns 32-key tiles.  K rows of a tile are fetched with fully
 // coalesced 16-byte lanes (16 lanes per 256-byte row), written to a wave-private, XOR-swizzled
