@@ -758,6 +758,8 @@ struct EmitShared {
   int astar[64];    // the cut bin on the standard grid (the tile test), 0x7FFFFFFF for rows pass 2 leaves alone
   float lo[64], hi[64];   // d * c1 in [lo, hi): the key lies in the row's cut bin; >= hi: above it (the bin may be a fine one)
   int row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
+  int n_need, next;                       // tiles of the piece that pass 2 has to look at, and how many have been taken
+  unsigned short tlist[kMaxChunkWords];   // ... their numbers inside the piece
 };
 
 template <int DK, bool TWO>
@@ -802,23 +804,31 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) cdst[nb] = tab.cands + ((size_t)grow[nb] * tab.sub_per_row + sub) * kSubCap;
 
-  uint32_t todo = need;        // tiles not yet fetched
+  // The tiles to look at go into one list for the workgroup; the waves then take them one at a time from a
+  // shared counter, so a wave whose own tiles mostly drop out helps with the others' (the tiles that matter
+  // are clustered).  No workgroup barrier inside the loop.
+  {
+    int base = 0;
+    if (lane == 0 && need != 0u) base = atomicAdd(&E->n_need, __popc(need));
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (lane < 32 && ((need >> lane) & 1u)) E->tlist[base + __popc(need & ((1u << lane) - 1u))] = (unsigned short)(wave + kWaves * lane);
+  }
+  __syncthreads();
+  const int n_need = E->n_need;
+  volatile lds_int *next = (volatile lds_int *)(size_t)lds_offset(&E->next);
   auto next_k = [&]() __attribute__((always_inline)) -> int {
-    if (todo == 0u) return -1;
-    const int k = __ffs(todo) - 1;
-    todo &= todo - 1u;
-    return k;
+    int gi = 0;
+    if (lane == 0) gi = __hip_atomic_fetch_add((lds_int *)next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    gi = __builtin_amdgcn_readfirstlane(gi);
+    return gi < n_need ? (int)E->tlist[gi] : -1;
   };
-  // No workgroup barrier inside the loop: waves with few tiles to look at finish early, the time of the
-  // pass follows the number of tiles that matter.
-  auto process = [&](u32x4(&pre)[LOADS], int k, int k_refill) __attribute__((always_inline)) {
-    const int tile = wave + kWaves * k;
+  auto process = [&](u32x4(&pre)[LOADS], int tile, int tile_refill) __attribute__((always_inline)) {
     const int t0 = c.t_begin + tile * 32;
     const int org = tile_origin(t0, c.t_end);
     const int skip = t0 - org;          // leading keys of the loaded window that are not this tile's
     T.stage(pre, ldstile, lane);
     {   // refill with the next tile to look at (or this one again: no conditional load)
-      const int tn = c.t_begin + (wave + kWaves * (k_refill >= 0 ? k_refill : k)) * 32;
+      const int tn = c.t_begin + (tile_refill >= 0 ? tile_refill : tile) * 32;
       T.fetch(pre, khead, I.tok_stride, tile_origin(tn, c.t_end), lane);
     }
     __builtin_amdgcn_wave_barrier();
@@ -880,8 +890,8 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   u32x4 pa[LOADS], pb[LOADS];
   int ka = next_k(), kb = next_k();
   if (ka >= 0) {
-    T.fetch(pa, khead, I.tok_stride, tile_origin(c.t_begin + (wave + kWaves * ka) * 32, c.t_end), lane);
-    T.fetch(pb, khead, I.tok_stride, tile_origin(c.t_begin + (wave + kWaves * (kb >= 0 ? kb : ka)) * 32, c.t_end), lane);
+    T.fetch(pa, khead, I.tok_stride, tile_origin(c.t_begin + ka * 32, c.t_end), lane);
+    T.fetch(pb, khead, I.tok_stride, tile_origin(c.t_begin + (kb >= 0 ? kb : ka) * 32, c.t_end), lane);
   }
   while (ka >= 0) {
     const int ka2 = next_k();
@@ -943,6 +953,7 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
         a >>= ri.shift;                               // (arithmetic shift = floor: the standard bin that holds the fine one)
       }
     }
+    if (tid == 0) { E.n_need = 0; E.next = 0; }
     E.astar[tid] = a;
     E.lo[tid] = lo;
     E.hi[tid] = hi;
