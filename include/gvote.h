@@ -144,6 +144,9 @@ GVOTE_API gvote_status gvote_sample_queries(const gvote_shape *shape, const gvot
  * rowmask: items back to back, item i holding [S * n_q_heads, W_i] words.
  * row_max, row_sum: optional [n_items, S * n_q_heads] fp32 diagnostics (m and Z), NULL to skip.
  * ws is required (gvote_workspace_bytes): statistics between the passes and the exact selector's logit cache.
+ * Range: on the matrix-core path logits beyond +-65536 (after the 1/sqrt(head_dim) scaling) are treated as +-65536
+ * by the histogram search; infinities and NaN in q or K never cause an invalid access, the affected rows' results are
+ * unspecified.
  * Diagnostics: when the matrix-core path runs (bf16, head_dim 64 or 128, every L >= 32; TOPP with p < 1, or TOPK) the first int32
  * words of ws hold, after the call and until ws is used again: [0] the number of rows that had to be redone by
  * the exact general selector, and [2..5] that number by reason: the cut lies below the histogram windows (two

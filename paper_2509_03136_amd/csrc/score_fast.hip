@@ -91,6 +91,12 @@ __device__ __forceinline__ int lds_offset(const void *p) {
 // t0 - origin of them, which belong to the previous tile or chunk, are ignored.
 __device__ __forceinline__ int tile_origin(int t0, int end) { return min(t0, end - 32); }
 
+// Bin number of a scaled dot for the window logic.  Bin numbers are kept inside +-2^20 (65536 logit units) whatever
+// the data holds (huge values, infinities, NaN -> the lower limit): LDS addresses are formed as 4 * bin + offset in
+// fp32, which is exact only for small integers, and an address outside the workgroup's LDS must never be issued.
+constexpr float kBinLimit = 1048576.0f;
+__device__ __forceinline__ int bin_of(float y) { return (int)fminf(fmaxf(floorf(y), -kBinLimit), kBinLimit); }
+
 // position of accumulator register r of lane (hf = lane / 32) inside the 32-key tile
 __device__ __forceinline__ int key_of(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
@@ -227,6 +233,7 @@ constexpr int kTopUnset = -(1 << 24);
 constexpr int kTopGaveUp = -(1 << 25);   // part_top of a (slot, row) whose pass-1 workgroup gave up: find_bin sends the row to the exact selector
 constexpr int kHeadroom = 4 * kBinsPerUnit;
 constexpr int kFineShift = 8, kFineBins = 1 << kFineShift;   // bins inside a cut bin: 1/4096 of a logit unit
+constexpr int kFineSpan = 1 << 13;     // |bin| below which fine bin numbers (x 256, x 4 bytes) stay exact in the fp32 address arithmetic: 512 logit units
 constexpr int kFineTrigger = 3500;     // keys in a cut bin beyond which it is looked into (the resolver holds kCandCap = 4096)
 constexpr int kRefineLevels = 1;        // further 256-bin windows below the first for rows whose cut lies deeper (one more
                                         // reaches 28..32 units below the maximum: weights of e^-28, beyond what fp32 sums resolve;
@@ -255,7 +262,7 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
     __syncthreads();
     for (int rr = 0; rr < 8; ++rr) {
       const int row = 8 * wave + rr;
-      const int amax = (int)floorf(from_ordered_bits(S->newmax[row]) * c1);
+      const int amax = bin_of(from_ordered_bits(S->newmax[row]) * c1);
       const int oldtop = S->top[row];
       if (amax > oldtop) {            // wave-uniform
         const int newtop = amax + kHeadroom;
@@ -322,10 +329,10 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
     mx1 = fmaxf(mx1, __shfl_xor(mx1, 32, 64));
     mxrun[0] = fmaxf(mxrun[0], mx0);
     mxrun[1] = fmaxf(mxrun[1], mx1);
-    const int amx0 = (int)floorf(mx0 * c1), amx1 = TWO ? (int)floorf(mx1 * c1) : 0;
+    const int amx0 = bin_of(mx0 * c1), amx1 = TWO ? bin_of(mx1 * c1) : 0;
     if (lane < 32) {        // bin of the largest dot of every (tile, row): pass 2 skips tiles no row needs
       short *tm = tab.tile_bin + I.tmax0 + ((size_t)c.kvh * I.W + (c.t_begin >> 5) + tile) * tab.NQ + c.n0 + col;
-      if (c.n0 + col < tab.NQ) tm[0] = (short)max(-32768, min(32767, amx0));      // (clamping only ever keeps a tile)
+      if (c.n0 + col < tab.NQ) tm[0] = (short)max(-32768, min(32767, amx0));      // (saturated: pass 2 caps its side of the test at 32767, so saturation only ever keeps a tile)
       if (TWO && c.n0 + 32 + col < tab.NQ) tm[32] = (short)max(-32768, min(32767, amx1));
     }
     const bool over0 = amx0 > top[0];
@@ -348,12 +355,12 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         if (nb == 0 || TWO) {
-          const float atail = (float)(top[nb] - (kBins - 1));
+          const float atail = (float)(top[nb] - (kBins - 1)), atop = (float)top[nb];
           const float abase = (float)(lds_offset(hrow[nb]) + 4 * top[nb]);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float d = acc[nb][r];
-            const float af = fmaxf(floorf(d * c1), atail);
+            const float af = __builtin_amdgcn_fmed3f(floorf(d * c1), atail, atop);     // (never above the top once the window has been raised: the upper clamp only keeps the address inside the row whatever the data)
             uint32_t u = 1u;        // TOPK counts keys
             if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
             lds_add_u32((uint32_t)fmaf(af, -4.0f, abase), u);
@@ -365,12 +372,12 @@ __device__ __forceinline__ void hist_fused_body(const FastTable &tab, const WgCo
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         if (nb == 0 || TWO) {
-          const float atail = (float)(top[nb] - (kBins - 1));
+          const float atail = (float)(top[nb] - (kBins - 1)), atop = (float)top[nb];
           const float abase = (float)(lds_offset(hrow[nb]) + 4 * top[nb]);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float d = acc[nb][r];
-            const float af = fmaxf(floorf(d * c1), atail);
+            const float af = __builtin_amdgcn_fmed3f(floorf(d * c1), atail, atop);     // (never above the top once the window has been raised: the upper clamp only keeps the address inside the row whatever the data)
             uint32_t u = 1u;
             if (!TOPK) u = (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, c2, fmaf(af, -kLog2ePerBin, ebias)));
             if (key_of(r, hf) < skip) u = 0u;
@@ -534,10 +541,12 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
     k = k < 1 ? 1 : (k > I.L ? I.L : k);
     target = (double)k;
   }
+  bool found = false;
 #pragma unroll
   for (int i = 0; i < BPL; ++i) {
     const int j = lane + 64 * i;
     const double before = cum[i] - mine[i];
+    found = found || (before < target && cum[i] >= target);
     if (!gave_up && before < target && cum[i] >= target) {
       info->mdot = m;
       info->astar = top - j;
@@ -555,11 +564,21 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
       const int n_sub = I.n_chunks * tab.emit_split * 2 * kWaves;
       const double fill = n_sub <= 64 ? 18.0 : (n_sub <= 160 ? 15.0 : (n_sub <= 512 ? 13.0 : 11.0));
       const double room = fmin((double)kFineTrigger, fill * (double)n_sub);
-      if (flag == 0 && in_bin > room) flag = 4;
+      if (flag == 0 && in_bin > room && abs(top - j) < kFineSpan) flag = 4;    // (beyond kFineSpan the row goes on as it is)
       info->flag = flag;
       if (flag != 0) atomicAdd(tab.n_refine, 1);     // asks for a second histogram (score_refine_kernel)
       info->above = before;
       info->target = target;
+    }
+  }
+  if (!gave_up && !__any(found)) {      // cannot happen (Z holds at least the largest key's weight, a count is at least 1): never
+    if (lane == 0) {                    // leave a row without a record, hand it to the exact selector like a row that gave up
+      info->mdot = m;
+      info->astar = 0x7FFFFFFF;
+      info->shift = 0;
+      info->flag = 7;
+      info->above = 0.0;
+      info->target = 0.0;
     }
   }
   if (lane == 0) {
@@ -662,8 +681,10 @@ __global__ __launch_bounds__(kThreads) void score_refine_kernel(const FastTable 
     if (n < tab.NQ) {
       const int s = n / tab.G, g = n % tab.G;
       const RowInfo &ri = tab.info[c.it * tab.rows_per_item + s * tab.Hq + c.kvh * tab.G + g];
-      if (ri.flag == 1) { t = ri.astar; any_s = 1; }      // astar of a flag-1 row = its window's last bin
-      if (ri.flag == 4) { t = (ri.astar + 1) * kFineBins - 1; sh = kFineShift; any_s = 1; }   // the finest bin under the cut bin's upper edge
+      // (bin numbers stay far inside +-2^21, where 4 * top + LDS offset is exact in fp32; anything else is not a
+      // record find_bin wrote and is left alone)
+      if (ri.flag == 1 && abs(ri.astar) < (1 << 21)) { t = ri.astar; any_s = 1; }      // astar of a flag-1 row = its window's last bin
+      if (ri.flag == 4 && abs(ri.astar) < kFineSpan) { t = (ri.astar + 1) * kFineBins - 1; sh = kFineShift; any_s = 1; }   // the finest bin under the cut bin's upper edge
     }
     top_s[tid] = t;
     shift_s[tid] = sh;
@@ -689,6 +710,10 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
   if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
   if (info->flag != 1 && info->flag != 4) return;
+  if ((info->flag == 1 && abs(info->astar) >= (1 << 21)) || (info->flag == 4 && abs(info->astar) >= kFineSpan)) {
+    if (lane == 0 && info->flag == 4) info->flag = 5;    // (score_refine_kernel left such a record alone: the exact selector takes the row)
+    return;
+  }
   const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
   const int s = r / tab.Hq, h = r - s * tab.Hq;
   const int kvh = h / tab.G, g = h - kvh * tab.G;
@@ -951,6 +976,7 @@ __global__ __launch_bounds__(kThreads) void score_emit_kernel(const FastTable ta
         lo = ldexpf((float)a, -ri.shift);            // exact: |a| < 2^24
         hi = ldexpf((float)a + 1.0f, -ri.shift);
         a >>= ri.shift;                               // (arithmetic shift = floor: the standard bin that holds the fine one)
+        a = min(a, 32767);                            // pass 1 stored the tile bins as int16, saturated: a saturated tile must pass the test
       }
     }
     if (tid == 0) { E.n_need = 0; E.next = 0; }

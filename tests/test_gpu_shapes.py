@@ -229,6 +229,35 @@ def test_second_histogram_on_full_and_partial_row_blocks(g, shape):
     assert n_ref > 0 and why[0] == 0
 
 
+def test_large_logits_stay_exact(g):
+    """Keys forty and four hundred times larger than the recipe's (and with the sign flipped): logits of several
+    hundred to ten thousand units, bin numbers far beyond what the int16 tile bins hold (the histogram grid is
+    absolute), windows raised in big jumps."""
+    wl = W.scaled(W.config(2), lengths=(3000, 500), n_planted=(40, 6), S=8)
+    items = W.make_items(wl, "cpu")
+    refs = [U.oracle_item(wl, it, upto="q") for it in items]
+    for scale in (40.0, 400.0, -400.0):
+        big = [dict(it, k=(it["k"].to(torch.float32) * scale).to(it["k"].dtype)) for it in items]
+        lgs = [O.scores(r["q_tilde"], U.f32np(it["k"])) for it, r in zip(big, refs)]
+        b = U.batch_from(g, wl, U.to_device(big, DEV))
+        pipe = g.Pipeline(b, wl.S, 0.9)
+        pipe.q.copy_(torch.tensor(np.stack([r["q_tilde"] for r in refs])).to(pipe.q.dtype))
+        pipe.select()
+        torch.cuda.synchronize()
+        off = nb = 0
+        for i, it in enumerate(big):
+            gm = U.unpack_rows(pipe.rowmask[off:off + pipe.mask_words[i]], pipe.rows, it["L"]).reshape(wl.S, wl.n_q_heads, it["L"])
+            off += pipe.mask_words[i]
+            # fp32 accumulation of a 128-term dot product: the logit error grows with the logit (about 2^-21 |l|), and
+            # an error of delta in a logit is an error of delta in its share of the mass
+            tol = max(U.STAGE_TOL["bf16"], 2.0 ** -21 * float(np.abs(lgs[i]).max()))
+            nb += U.check_rowmask_strict(gm, lgs[i], U.p32(0.9), tol)
+            m = lgs[i].max(-1).reshape(-1)
+            assert np.all(np.abs(pipe.row_max[i].cpu().numpy() - m) <= U.STAGE_TOL["bf16"] * (1 + np.abs(m)))
+        say(f"  keys x {scale:g}: largest |logit| {max(np.abs(l).max() for l in lgs):.0f}, boundary keys {nb}, "
+            f"redone exactly {pipe.fallback_rows()} {pipe.fallback_reasons()}")
+
+
 def test_crowded_cut_bin_is_looked_into_with_finer_bins(g):
     """Nearly flat attention over a long context: thousands of keys share the 1/16-logit bin of the cut, more than the
     candidate resolver holds.  The bin is then split into 256 finer ones (a second histogram pass) instead of handing
