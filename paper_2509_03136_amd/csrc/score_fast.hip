@@ -702,12 +702,8 @@ __global__ __launch_bounds__(kThreads) void score_refine_kernel(const FastTable 
   for (int i = tid; i < rows * kBins; i += kThreads) out[i] = hist[(i / kBins) * (kBins + 1) + (i % kBins)];
 }
 
-// one wave per row: continue the cumulative search of a flag-1 row in its refined window
-__global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastTable tab, int n_rows, int level) {
-  if (tab.n_refine[level] == 0) return;
-  const int lane = threadIdx.x & 63;
-  const int grow = blockIdx.x * kFindWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (grow >= n_rows) return;
+// one wave per row: continue the cumulative search of a flagged row in its second histogram
+__device__ __forceinline__ void refine_row(const FastTable &tab, int grow, int level, int lane) {
   RowInfo *info = tab.info + grow;
   if (info->flag != 1 && info->flag != 4) return;
   if ((info->flag == 1 && abs(info->astar) >= (1 << 21)) || (info->flag == 4 && abs(info->astar) >= kFineSpan)) {
@@ -771,6 +767,14 @@ __global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastT
       }
     }
   }
+}
+
+// a small grid walks the rows (the launch costs little when nobody asked)
+constexpr int kRefineBinGrid = 512;
+__global__ __launch_bounds__(kFindWaves * 64) void refine_bin_kernel(const FastTable tab, int n_rows, int level) {
+  if (tab.n_refine[level] == 0) return;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  for (int grow = blockIdx.x * kFindWaves + wave; grow < n_rows; grow += gridDim.x * kFindWaves) refine_row(tab, grow, level, lane);
 }
 
 // ------------------------------------------------------------------ pass 2: masks + boundary candidates
@@ -1260,7 +1264,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
         if (topk) hipLaunchKernelGGL((score_refine_kernel<128, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
         else hipLaunchKernelGGL((score_refine_kernel<128, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
         GVOTE_CHECK_LAUNCH();
-        hipLaunchKernelGGL(refine_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
+        hipLaunchKernelGGL(refine_bin_kernel, dim3(min(ceil_div(rows, kFindWaves), kRefineBinGrid)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
         GVOTE_CHECK_LAUNCH();
       }
       hipLaunchKernelGGL(score_emit_kernel<128>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
@@ -1274,7 +1278,7 @@ gvote_status launch_score_fast(const gvote_shape *sh, const gvote_item *items, i
         if (topk) hipLaunchKernelGGL((score_refine_kernel<64, true>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
         else hipLaunchKernelGGL((score_refine_kernel<64, false>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
         GVOTE_CHECK_LAUNCH();
-        hipLaunchKernelGGL(refine_bin_kernel, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
+        hipLaunchKernelGGL(refine_bin_kernel, dim3(min(ceil_div(rows, kFindWaves), kRefineBinGrid)), dim3(kFindWaves * 64), 0, st, tab, rows, lvl);
         GVOTE_CHECK_LAUNCH();
       }
       hipLaunchKernelGGL(score_emit_kernel<64>, dim3(grid_wg * tab.emit_split), dim3(kThreads), 0, st, tab);
