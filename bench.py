@@ -62,7 +62,7 @@ def profiled_traffic(workload, kernel):
         if line.startswith(kernel):
             cols = line[38:].split()
             try:
-                return (float(cols[2]) + float(cols[3])) * 1e6
+                return (float(cols[-2]) + float(cols[-1])) * 1e6     # the last two columns: MB read, MB written
             except (IndexError, ValueError):
                 return None
     return None
@@ -239,6 +239,7 @@ def main():
         traffic = (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
     else:
         traffic = profiled_traffic(wl.name, dom_kernel) if not over and not args.items and not args.length else None
+    step_traffic = profiled_traffic(wl.name, "whole step") if traffic is not None and args.traffic_kib is None else None
     ach = ab[dom] / (stage_ms[dom] * 1e-3) / 1e9
     copy_gbs = copy_ceiling(torch, dev)
     e2e_gbs = ab["total"] / (ms_per_step * 1e-3) / 1e9
@@ -257,7 +258,11 @@ def main():
                      "algorithmic_bytes": ab[dom], "ms": stage_ms[dom]},
         "end_to_end": {"algorithmic_GB": ab["total"] / 1e9, "achieved_GBs": e2e_gbs,
                        "frac_of_hbm_peak": e2e_gbs / HBM_PEAK_GBS,
-                       "copy_ceiling_GBs": copy_gbs, "frac_of_copy_ceiling": e2e_gbs / copy_gbs},
+                       "copy_ceiling_GBs": copy_gbs, "frac_of_copy_ceiling": e2e_gbs / copy_gbs,
+                       # HBM bytes of a whole step from the committed counter runs, and the rate they mean at this step time
+                       "traffic": step_traffic,
+                       "traffic_GBs": None if step_traffic is None else step_traffic / (ms_per_step * 1e-3) / 1e9},
+        "head_tokens_per_s": tok * wl.n_kv_heads / (ms_per_step * 1e-3),
         "stage_ms": stage_ms,
         "stage_algorithmic_GBs": {k: ab[k] / (stage_ms[k] * 1e-3) / 1e9 for k in stage_ms},
         "stage_frac_of_hbm_peak": {k: ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS for k in stage_ms},
