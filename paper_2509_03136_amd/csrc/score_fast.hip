@@ -793,6 +793,7 @@ struct EmitShared {
   float lo[64], hi[64];   // d * c1 in [lo, hi): the key lies in the row's cut bin; >= hi: above it (the bin may be a fine one)
   int row[64];      // row index (s * H_q + h) of the workgroup's 64 query rows, -1 if absent
   int n_need, next;                       // tiles of the piece that pass 2 has to look at, and how many have been taken
+  uint32_t need_w[kWaves];                // per wave: which of its tiles
   unsigned short tlist[kMaxChunkWords];   // ... their numbers inside the piece
 };
 
@@ -841,11 +842,22 @@ __device__ __forceinline__ void emit_body(const FastTable &tab, const WgCoord &c
   // The tiles to look at go into one list for the workgroup; the waves then take them one at a time from a
   // shared counter, so a wave whose own tiles mostly drop out helps with the others' (the tiles that matter
   // are clustered).  No workgroup barrier inside the loop.
+  // The list is in ascending key order (the same on every run; the row blocks of one chunk, which run side by side,
+  // sweep the keys together).
+  if (lane == 0) E->need_w[wave] = need;
+  __syncthreads();
   {
-    int base = 0;
-    if (lane == 0 && need != 0u) base = atomicAdd(&E->n_need, __popc(need));
-    base = __builtin_amdgcn_readfirstlane(base);
-    if (lane < 32 && ((need >> lane) & 1u)) E->tlist[base + __popc(need & ((1u << lane) - 1u))] = (unsigned short)(wave + kWaves * lane);
+    // tile wave + 8 k comes after every tile (w', k') with k' < k, and after those with k' == k and w' < wave
+    int before = 0, total = 0;
+    const uint32_t lower = lane < 32 ? (1u << lane) - 1u : 0xFFFFFFFFu;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t nw = E->need_w[w];
+      total += __popc(nw);
+      before += __popc(nw & lower) + ((w < wave && lane < 32) ? (int)((nw >> lane) & 1u) : 0);
+    }
+    if (lane < 32 && ((need >> lane) & 1u)) E->tlist[before] = (unsigned short)(wave + kWaves * lane);
+    if (threadIdx.x == 0) E->n_need = total;
   }
   __syncthreads();
   const int n_need = E->n_need;
