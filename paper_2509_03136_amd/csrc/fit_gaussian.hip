@@ -82,23 +82,37 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
   }
 }
 
-__global__ __launch_bounds__(256) void moments_finalize_kernel(const FitTable tab, int ddof, float *mu, float *var,
-                                                               int item0) {
+// Chan merge of the chunks in fp64, in a fixed order: 32 channels per workgroup, eight threads per channel each merge
+// every eighth chunk, then thread 0 of the channel merges the eight partial results (a long single item has hundreds of
+// chunks: one thread walking them all took longer than the pass over the hidden states).
+constexpr int kFinCh = 32, kFinLanes = 8;
+__device__ __forceinline__ void chan_merge(double &n, double &mean, double &m2, double nb, double mb, double vb) {
+  if (nb <= 0.0) return;
+  const double nn = n + nb, delta = mb - mean, r = nb / nn;
+  mean += delta * r;
+  m2 += vb + delta * delta * (n * r);
+  n = nn;
+}
+__global__ __launch_bounds__(kFinCh * kFinLanes) void moments_finalize_kernel(const FitTable tab, int ddof, float *mu,
+                                                                             float *var, int item0) {
+  __shared__ double sn[kFinLanes][kFinCh], smean[kFinLanes][kFinCh], sm2[kFinLanes][kFinCh];
   const int it = blockIdx.y;
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= tab.d) return;
+  const int ch = threadIdx.x % kFinCh, cl = threadIdx.x / kFinCh;
+  const int col = blockIdx.x * kFinCh + ch;
   const FitItem I = tab.it[it];
   double n = 0.0, mean = 0.0, m2 = 0.0;
-  for (int c = 0; c < I.n_chunks; ++c) {
-    const int r0 = I.n_skip + c * tab.rows_per_chunk;
-    const double nb = (double)(min(I.L, r0 + tab.rows_per_chunk) - r0);
-    const float *pm = tab.partial + ((size_t)(I.chunk0 + c) * 2) * tab.d + col;
-    const double mb = (double)pm[0], vb = (double)pm[tab.d];
-    const double nn = n + nb, delta = mb - mean;
-    mean += delta * (nb / nn);
-    m2 += vb + delta * delta * (n * nb / nn);
-    n = nn;
+  if (col < tab.d) {
+    for (int c = cl; c < I.n_chunks; c += kFinLanes) {
+      const int r0 = I.n_skip + c * tab.rows_per_chunk;
+      const double nb = (double)(min(I.L, r0 + tab.rows_per_chunk) - r0);
+      const float *pm = tab.partial + ((size_t)(I.chunk0 + c) * 2) * tab.d + col;
+      chan_merge(n, mean, m2, nb, (double)pm[0], (double)pm[tab.d]);
+    }
   }
+  sn[cl][ch] = n; smean[cl][ch] = mean; sm2[cl][ch] = m2;
+  __syncthreads();
+  if (cl != 0 || col >= tab.d) return;
+  for (int l = 1; l < kFinLanes; ++l) chan_merge(n, mean, m2, sn[l][ch], smean[l][ch], sm2[l][ch]);
   mu[(size_t)(item0 + it) * tab.d + col] = (float)mean;
   var[(size_t)(item0 + it) * tab.d + col] = (float)(m2 / (n - (double)ddof));
 }
@@ -164,8 +178,8 @@ gvote_status launch_fit(const gvote_shape *sh, const gvote_item *items, int n_it
     else
       hipLaunchKernelGGL(moments_partial_kernel<bf16_t>, grid, dim3(kFitThreads), 0, st, tab);
     GVOTE_CHECK_LAUNCH();
-    hipLaunchKernelGGL(moments_finalize_kernel, dim3(ceil_div(sh->d_model, 256), nb), dim3(256), 0, st, tab, ddof, mu,
-                       var, b0);
+    hipLaunchKernelGGL(moments_finalize_kernel, dim3(ceil_div(sh->d_model, kFinCh), nb), dim3(kFinCh * kFinLanes), 0, st, tab,
+                       ddof, mu, var, b0);
     GVOTE_CHECK_LAUNCH();
     chunk_done += c;
   }
