@@ -5,7 +5,7 @@ A step = one pass of the whole path (fit -> sample/project/RoPE -> score/select 
 over one batch of synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--beta B] [--S n] [--p x]
-                  [--sweep S|p] [--no-cpu-baseline] [--copy-probe]
+                  [--sweep S|p] [--graph] [--no-cpu-baseline] [--copy-probe]
 
 metric: layer-tokens per second = (sum over items of context length L) / step time.
 roofline: the stage that dominates the step, priced on ALGORITHMIC bytes against 8 TB/s HBM.
@@ -181,6 +181,8 @@ def main():
                     help="also time Algorithm 1 as printed: top-p of one real query per head -> B_step -> row-wise "
                          "TopK of the synthetic rows -> union / compaction (the first synthetic sample stands in "
                          "for the real current query)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the four stage calls into a HIP graph and time its replays (the calls only enqueue kernels)")
     ap.add_argument("--cpu-sample", type=int, default=8, help="items the CPU oracle is timed on (about 1.3 s each at config 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -274,6 +276,24 @@ def main():
         "compressed_bytes": kept * wl.d_k * wl.elem_bytes * 2,
         "input_generation_s": t_gen,
     }
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            pipe.run()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            pipe.run()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
     if args.consumer:
         qd = torch.randn(wl.n_items, wl.n_q_heads, wl.d_k, device=dev, dtype=torch.float32).to(pipe.q.dtype)
         od = torch.empty_like(qd)
