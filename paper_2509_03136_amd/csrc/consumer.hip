@@ -445,9 +445,10 @@ size_t overlap_ws_bytes(const gvote_shape *sh, const gvote_item *items, int n_it
 }
 
 int decode_splits(const gvote_shape *sh, int n_items) {
-  // about eight workgroups per CU over the call, at most 64 shares per head
+  // about two workgroups per CU over the call (measured on 256 heads of ~4000 rows: 256..512 workgroups 0.095 ms,
+  // 1024 0.099, 2048 0.111, 4096 0.136), at most 64 shares per head
   const int heads = n_items * sh->n_kv_heads;
-  int s = (2048 + heads - 1) / heads;
+  int s = (512 + heads - 1) / heads;
   return s < 1 ? 1 : (s > 64 ? 64 : s);
 }
 
