@@ -367,11 +367,21 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
         }
         if (tab.grp_count[tab.n_groups - 1] > widest) widest = tab.grp_count[tab.n_groups - 1];
       }
-      const dim3 gp(ceil_div(n_out, kProjWaves * 32), plan.ksplits, tab.n_groups);
       const int nsb = (widest * S + 31) / 32;
-      const size_t lds = (size_t)(32 * nsb) * (plan.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
+      // A product of up to 32 columns can take slices of 1024 channels (99 KB of LDS): half the partial sums for
+      // rope_finalize to read, -8 % on the stage.  Only when 1024 divides the hidden size (a shorter last slice takes
+      // the slow guarded path); the workspace is sized for the 512-channel slices either way.
+      if (nsb == 1 && plan.kslice == 512 && sh->d_model % 1024 == 0) {
+        tab.kslice = 1024;
+        tab.ksplits = sh->d_model / 1024;
+      }
+      const dim3 gp(ceil_div(n_out, kProjWaves * 32), tab.ksplits, tab.n_groups);
+      const size_t lds = (size_t)(32 * nsb) * (tab.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
       if (lds > kLdsBytesPerCu) return GVOTE_ERR_CAPACITY;       // cannot happen with the slices plan_sample picks
       hipError_t attr = hipSuccess;                               // more than 64 KiB of dynamic LDS must be asked for
+      if (nsb == 1 && lds > 65536)
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<1>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 2 && lds > 65536)
         attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
