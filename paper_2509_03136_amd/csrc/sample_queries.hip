@@ -87,9 +87,11 @@ __global__ __launch_bounds__(256) void sample_hidden_kernel(const SampleTable ta
 // ---- bf16 MFMA projection.  grid (ceil(n_out/256), ksplits, item groups), 512 threads (8 waves x 32 outputs).
 // A group is a run of items with the same W_q; its n x S sampled states (contiguous in the workspace) are the
 // columns of one product.
-constexpr int kProjWaves = 8;
-template <int NSB>
-__global__ __launch_bounds__(kProjWaves * 64) void project_mfma_kernel(const SampleTable tab) {
+// WAVES: 8, or 16 for a single 32-column block (the staged columns are then shared by 512 outputs and a CU still
+// holds sixteen waves when the 1024-channel slice leaves room for only one workgroup)
+template <int NSB, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void project_mfma_kernel(const SampleTable tab) {
+  constexpr int kProjWaves = WAVES;
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t *Bs = reinterpret_cast<bf16_t *>(smem);   // [32*NSB][kslice + 8]
   const int it = tab.grp_first[blockIdx.z], ks = blockIdx.y;
@@ -371,35 +373,42 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
       // A product of up to 32 columns can take slices of 1024 channels (99 KB of LDS): half the partial sums for
       // rope_finalize to read, -8 % on the stage.  Only when 1024 divides the hidden size (a shorter last slice takes
       // the slow guarded path); the workspace is sized for the 512-channel slices either way.
-      if (nsb == 1 && plan.kslice == 512 && sh->d_model % 1024 == 0) {
+      // Both only pay when the grid still fills the chip twice over (a single layer has few workgroups as it is).
+      const long long wgs8 = (long long)ceil_div(n_out, 8 * 32) * tab.n_groups;      // per k-slice, 8-wave workgroups
+      if (nsb == 1 && plan.kslice == 512 && sh->d_model % 1024 == 0 && wgs8 * (sh->d_model / 1024) >= 1024) {
         tab.kslice = 1024;
         tab.ksplits = sh->d_model / 1024;
       }
-      const dim3 gp(ceil_div(n_out, kProjWaves * 32), tab.ksplits, tab.n_groups);
-      const size_t lds = (size_t)(32 * nsb) * (tab.kslice + 8) * sizeof(bf16_t) + kProjWaves * 4096;
+      const int waves = (nsb == 1 && tab.kslice == 1024 && wgs8 / 2 * tab.ksplits >= 512) ? 16 : 8;
+      const dim3 gp(ceil_div(n_out, waves * 32), tab.ksplits, tab.n_groups);
+      const size_t lds = (size_t)(32 * nsb) * (tab.kslice + 8) * sizeof(bf16_t) + waves * 4096;
       if (lds > kLdsBytesPerCu) return GVOTE_ERR_CAPACITY;       // cannot happen with the slices plan_sample picks
       hipError_t attr = hipSuccess;                               // more than 64 KiB of dynamic LDS must be asked for
       if (nsb == 1 && lds > 65536)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<1>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr = waves == 16 ? hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<1, 16>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                           : hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<1, 8>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 2 && lds > 65536)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<2>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<2, 8>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 3)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<3, 8>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (nsb == 4)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(project_mfma_kernel<4, 8>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (attr != hipSuccess) return GVOTE_ERR_HIP;
-      if (nsb == 1)
-        hipLaunchKernelGGL(project_mfma_kernel<1>, gp, dim3(kProjWaves * 64), lds, st, tab);
+      if (nsb == 1 && waves == 16)
+        hipLaunchKernelGGL((project_mfma_kernel<1, 16>), gp, dim3(waves * 64), lds, st, tab);
+      else if (nsb == 1)
+        hipLaunchKernelGGL((project_mfma_kernel<1, 8>), gp, dim3(waves * 64), lds, st, tab);
       else if (nsb == 2)
-        hipLaunchKernelGGL(project_mfma_kernel<2>, gp, dim3(kProjWaves * 64), lds, st, tab);
+        hipLaunchKernelGGL((project_mfma_kernel<2, 8>), gp, dim3(waves * 64), lds, st, tab);
       else if (nsb == 3)
-        hipLaunchKernelGGL(project_mfma_kernel<3>, gp, dim3(kProjWaves * 64), lds, st, tab);
+        hipLaunchKernelGGL((project_mfma_kernel<3, 8>), gp, dim3(waves * 64), lds, st, tab);
       else
-        hipLaunchKernelGGL(project_mfma_kernel<4>, gp, dim3(kProjWaves * 64), lds, st, tab);
+        hipLaunchKernelGGL((project_mfma_kernel<4, 8>), gp, dim3(waves * 64), lds, st, tab);
     } else {
       const dim3 gp(ceil_div(n_out, 4), nb);
       if (sh->dtype == GVOTE_F32)
