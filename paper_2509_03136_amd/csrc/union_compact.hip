@@ -152,17 +152,30 @@ __global__ __launch_bounds__(256) void gather_kernel(const UnionTable tab) {
   T *vo = reinterpret_cast<T *>(tab.v_out);
   constexpr int EPP = 16 / (int)sizeof(T);       // elements per piece
   if (rsel < rows_per_step) {
-    for (int i = rsel; i < n; i += rows_per_step) {
-      const long long dst = base + i;
-      if (dst >= tab.capacity) break;
-      const int t = list[i];
-      const long long src = (long long)t * I.tok_stride + piece * EPP;
-      // kept rows are read once and written once: non-temporal both ways, the caches stay with W_q
-      const u32x4_t kx = load_stream16(kb + src);
-      const u32x4_t vx = load_stream16(vb + src);
-      __builtin_nontemporal_store(kx, reinterpret_cast<u32x4_t *>(ko + dst * dk + piece * EPP));
-      __builtin_nontemporal_store(vx, reinterpret_cast<u32x4_t *>(vo + dst * dk + piece * EPP));
-      if (piece == 0 && tab.idx_out) tab.idx_out[dst] = t;
+    // kept rows are read once and written once: non-temporal both ways, the caches stay with W_q.  Four rows per
+    // thread are in flight before the first is written.
+    constexpr int U = 4;
+    for (int i0 = rsel; i0 < n; i0 += U * rows_per_step) {
+      int t[U];
+      u32x4_t kx[U], vx[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + u * rows_per_step;
+        t[u] = list[i < n ? i : n - 1];
+        const long long src = (long long)t[u] * I.tok_stride + piece * EPP;
+        kx[u] = load_stream16(kb + src);
+        vx[u] = load_stream16(vb + src);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + u * rows_per_step;
+        const long long dst = base + i;
+        if (i < n && dst < tab.capacity) {
+          __builtin_nontemporal_store(kx[u], reinterpret_cast<u32x4_t *>(ko + dst * dk + piece * EPP));
+          __builtin_nontemporal_store(vx[u], reinterpret_cast<u32x4_t *>(vo + dst * dk + piece * EPP));
+          if (piece == 0 && tab.idx_out) tab.idx_out[dst] = t[u];
+        }
+      }
     }
   }
 }
