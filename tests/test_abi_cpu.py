@@ -142,3 +142,24 @@ def test_missing_library_is_a_loud_error(g, monkeypatch, tmp_path):
     monkeypatch.setattr(b, "_HERE", str(tmp_path))
     with pytest.raises(ImportError):
         b.lib()
+
+
+def test_bench_takes_traffic_only_from_profiles_of_these_kernel_sources(g):
+    """bench.py fills roofline.traffic from the committed counter summary of the workload, and only when that summary
+    carries the digest of the kernel sources in this tree (a summary of other sources must not be quoted)."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2509_03136_amd.build import sources_digest
+    path = os.path.join(ROOT, "profiles", "cfg3_llama8b_stack_32k_hbm_traffic_pmc.txt")
+    assert os.path.exists(path)
+    stamp = [l.split(":", 1)[1].strip() for l in open(path).read().splitlines() if l.startswith("kernel sources sha256:")]
+    assert len(stamp) == 1 and len(stamp[0]) == 16
+    got = bench.profiled_traffic("cfg3_llama8b_stack_32k", "moments_partial_kernel")
+    step = bench.profiled_traffic("cfg3_llama8b_stack_32k", "whole step")
+    if stamp[0] == sources_digest():
+        assert 8.5e9 < got < 9.5e9          # the fit reads the hidden states (8.59 GB) once
+        assert 12.9e9 < step < 20e9         # a step moves at least its algorithmic bytes
+    else:
+        assert got is None and step is None
+    assert bench.profiled_traffic("no_such_workload", "moments_partial_kernel") is None
