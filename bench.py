@@ -181,6 +181,9 @@ def main():
                     help="also time Algorithm 1 as printed: top-p of one real query per head -> B_step -> row-wise "
                          "TopK of the synthetic rows -> union / compaction (the first synthetic sample stands in "
                          "for the real current query)")
+    ap.add_argument("--kv-head-major", action="store_true",
+                    help="hold K and V as [H_kv, L, d_k] (a head's keys contiguous) instead of [L, H_kv, d_k]; the ABI takes "
+                         "either through its token and head strides")
     ap.add_argument("--graph", action="store_true",
                     help="also record the four stage calls into a HIP graph and time its replays (the calls only enqueue kernels)")
     ap.add_argument("--cpu-sample", type=int, default=8, help="items the CPU oracle is timed on (about 1.3 s each at config 3)")
@@ -220,6 +223,10 @@ def main():
     items = W.make_items(wl, dev)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    if args.kv_head_major:
+        for it in items:
+            for name in ("k", "v"):
+                it[name] = it[name].permute(1, 0, 2).contiguous().permute(1, 0, 2)      # same values, head-major memory
     b = g.Batch.from_workload(wl, items)
     pipe = g.Pipeline(b, wl.S, wl.p, ddof=wl.ddof, want_stats=False)
 
