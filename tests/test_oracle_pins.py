@@ -449,6 +449,22 @@ def test_mask_checks_reject_planted_mistakes():
     U.check_rowmask_sandwich(swapped[None, None, :], l2[None, None, :], p, tol)
     with pytest.raises(AssertionError):
         U.check_rowmask_strict(swapped[None, None, :], l2[None, None, :], p, tol)
+    # ... also when the tied pair is so heavy that the second key's interval starts beyond p + tol (two keys of 1 % each,
+    # logits 1e-5 apart: one query element rounding the other way swaps them); a key that is lighter by more than the
+    # score tolerance is no substitute
+    w3 = np.array([0.60, 0.30, 0.048, 0.0106, 0.0106 * (1 - 1e-5), 0.009] + [0.02180011 / 40] * 40)
+    l3 = np.log(w3)
+    sel = O.top_p_select(l3, p)
+    assert sel.sum() == 4 and sel[3] and not sel[4]
+    must, may = U.band_sets(l3, p, tol)
+    assert not may[4]                                                        # the band alone would refuse key 4
+    twin = sel.copy(); twin[3] = False; twin[4] = True
+    U.check_rowmask_sandwich(twin[None, None, :], l3[None, None, :], p, tol)
+    with pytest.raises(AssertionError):
+        U.check_rowmask_strict(twin[None, None, :], l3[None, None, :], p, tol)
+    lighter = sel.copy(); lighter[3] = False; lighter[5] = True             # 0.9 % instead of 1.06 %: logits 0.16 apart
+    with pytest.raises(AssertionError):
+        U.check_rowmask_sandwich(lighter[None, None, :], l3[None, None, :], p, tol)
     U.check_budgets([100, 4000], [104, 4080])
     with pytest.raises(AssertionError):
         U.check_budgets([100], [120])
