@@ -22,6 +22,8 @@
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue work: they
  *     never synchronise, so outputs are valid once the stream has reached that point.
  *     Calls that share a workspace must be issued on one stream (or otherwise ordered).
+ *     No call allocates, copies, clears memory through the runtime or waits: a caller may record
+ *     the calls into a HIP graph and replay it.
  *   - Errors are returned as gvote_status.  Everything that can be checked on the host (null
  *     pointers, shapes, alignment, workspace size, unsupported types) is rejected before any
  *     launch, leaving all outputs untouched.  A failing HIP launch gives GVOTE_ERR_HIP.

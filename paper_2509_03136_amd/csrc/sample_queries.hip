@@ -248,50 +248,59 @@ __global__ __launch_bounds__(256) void project_generic_kernel(const SampleTable 
   }
 }
 
-// ---- reduction over k-splits, bias, rotation, rounding.  grid (ceil(pairs/8), items), 256 threads
-template <typename T>
+// ---- reduction over k-splits, bias, rotation, rounding.  grid (query heads, items, blocks of 16 samples), 256
+// threads: one workgroup per head and sample block: the partial sums are read along the samples (they are contiguous per output), the
+// rotated pair goes into an LDS tile [sample][head_dim], and the tile is written out row by row, so that the stores
+// to Q~ are contiguous runs of a head instead of two-byte stores n_out apart.
+// kRopeSamples: 16, or 32 when there are more than 16 samples (a partial-sum row is then read whole by one workgroup)
+template <typename T, int kRopeSamples>
 __global__ __launch_bounds__(256) void rope_finalize_kernel(const SampleTable tab) {
-  const int it = blockIdx.y;
+  const int it = blockIdx.y, hd = blockIdx.x;
   const SampleItem I = tab.it[it];
-  const int half = tab.head_dim / 2;
-  const int n_pairs = (tab.n_out / tab.head_dim) * half;
-  __shared__ float cs[8][2];
-  if (threadIdx.x < 8) {
-    const int pr = blockIdx.x * 8 + threadIdx.x;
-    if (pr < n_pairs) {
-      const int i = pr % half;
-      const double omega = pow((double)tab.theta, -2.0 * (double)i / (double)tab.head_dim);
-      double c = 0.0, s = 0.0;
-      for (int tau = 0; tau < I.n_future; ++tau) {
-        const double ang = (double)(I.pos0 + tau) * omega;
-        c += cos(ang);
-        s += sin(ang);
-      }
-      cs[threadIdx.x][0] = (float)(c / (double)I.n_future);
-      cs[threadIdx.x][1] = (float)(s / (double)I.n_future);
+  const int dk = tab.head_dim, half = dk / 2;          // head_dim <= 256 (checked by the entry point)
+  __shared__ float cs[128][2];
+  __shared__ T tile[kRopeSamples][256];
+  for (int i = threadIdx.x; i < half; i += 256) {
+    const double omega = pow((double)tab.theta, -2.0 * (double)i / (double)dk);
+    double c = 0.0, s = 0.0;
+    for (int tau = 0; tau < I.n_future; ++tau) {
+      const double ang = (double)(I.pos0 + tau) * omega;
+      c += cos(ang);
+      s += sin(ang);
     }
+    cs[i][0] = (float)(c / (double)I.n_future);
+    cs[i][1] = (float)(s / (double)I.n_future);
   }
   __syncthreads();
-  const int slot = threadIdx.x >> 5;
-  const int pair = blockIdx.x * 8 + slot;
-  if (pair >= n_pairs) return;
-  const int hd = pair / half, i = pair % half;
-  const int o1 = hd * tab.head_dim + i, o2 = o1 + half;
-  const float c = cs[slot][0], sn = cs[slot][1];
   const T *bias = reinterpret_cast<const T *>(I.b_q);
-  const float b1 = bias ? to_f32<T>(bias[o1]) : 0.f, b2 = bias ? to_f32<T>(bias[o2]) : 0.f;
-  T *q = reinterpret_cast<T *>(tab.q_out) + (size_t)(tab.item0 + it) * tab.S * tab.n_out;
-  for (int s = threadIdx.x & 31; s < tab.S; s += 32) {
-    float a = 0.f, b = 0.f;
-    for (int ks = 0; ks < tab.ksplits; ++ks) {
-      const float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
-      a += part[(size_t)o1 * tab.SPs + s];
-      b += part[(size_t)o2 * tab.SPs + s];
+  T *q = reinterpret_cast<T *>(tab.q_out) + (size_t)(tab.item0 + it) * tab.S * tab.n_out + (size_t)hd * dk;
+  {
+    const int s0 = blockIdx.z * kRopeSamples;
+    for (int w = threadIdx.x; w < half * kRopeSamples; w += 256) {
+      const int sl = w % kRopeSamples, i = w / kRopeSamples, s = s0 + sl;
+      if (s < tab.S) {
+        const int o1 = hd * dk + i, o2 = o1 + half;
+        float a = 0.f, b = 0.f;
+#pragma unroll 4
+        for (int ks = 0; ks < tab.ksplits; ++ks) {
+          const float *part = tab.partial + ((size_t)(it * tab.ksplits + ks) * tab.n_out) * tab.SPs;
+          a += part[(size_t)o1 * tab.SPs + s];
+          b += part[(size_t)o2 * tab.SPs + s];
+        }
+        if (bias) {
+          a += to_f32<T>(bias[o1]);
+          b += to_f32<T>(bias[o2]);
+        }
+        const float c = cs[i][0], sn = cs[i][1];
+        tile[sl][i] = from_f32<T>(a * c - b * sn);
+        tile[sl][i + half] = from_f32<T>(b * c + a * sn);
+      }
     }
-    a += b1;
-    b += b2;
-    q[(size_t)s * tab.n_out + o1] = from_f32<T>(a * c - b * sn);
-    q[(size_t)s * tab.n_out + o2] = from_f32<T>(b * c + a * sn);
+    __syncthreads();
+    for (int e = threadIdx.x; e < kRopeSamples * dk; e += 256) {
+      const int r = e / dk, c = e - r * dk;
+      if (s0 + r < tab.S) q[(size_t)(s0 + r) * tab.n_out + c] = tile[r][c];
+    }
   }
 }
 
@@ -417,11 +426,15 @@ gvote_status launch_sample(const gvote_shape *sh, const gvote_item *items, int n
         hipLaunchKernelGGL(project_generic_kernel<bf16_t>, gp, dim3(256), 0, st, tab);
     }
     GVOTE_CHECK_LAUNCH();
-    const dim3 gf(ceil_div((n_out / sh->head_dim) * (sh->head_dim / 2), 8), nb);
-    if (sh->dtype == GVOTE_F32)
-      hipLaunchKernelGGL(rope_finalize_kernel<float>, gf, dim3(256), 0, st, tab);
-    else
-      hipLaunchKernelGGL(rope_finalize_kernel<bf16_t>, gf, dim3(256), 0, st, tab);
+    const int rope_block = S > 16 ? 32 : 16;
+    const dim3 gf(n_out / sh->head_dim, nb, ceil_div(S, rope_block));
+    if (sh->dtype == GVOTE_F32) {
+      if (rope_block == 32) hipLaunchKernelGGL((rope_finalize_kernel<float, 32>), gf, dim3(256), 0, st, tab);
+      else hipLaunchKernelGGL((rope_finalize_kernel<float, 16>), gf, dim3(256), 0, st, tab);
+    } else {
+      if (rope_block == 32) hipLaunchKernelGGL((rope_finalize_kernel<bf16_t, 32>), gf, dim3(256), 0, st, tab);
+      else hipLaunchKernelGGL((rope_finalize_kernel<bf16_t, 16>), gf, dim3(256), 0, st, tab);
+    }
     GVOTE_CHECK_LAUNCH();
   }
   return GVOTE_OK;
