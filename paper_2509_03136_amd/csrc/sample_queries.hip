@@ -101,13 +101,15 @@ __global__ __launch_bounds__(WAVES * 64) void project_mfma_kernel(const SampleTa
   const int ldb = tab.kslice + 8;
   const bf16_t *hsrc = reinterpret_cast<const bf16_t *>(tab.h_tilde) + (size_t)it * tab.S * tab.d + k0;
   const int vec_per_row = tab.kslice / 8;
-  for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += kProjWaves * 64) {
-    const int s = v / vec_per_row, kk = (v % vec_per_row) * 8;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (s < S_grp && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
-    *reinterpret_cast<uint4 *>(Bs + s * ldb + kk) = val;
-  }
-  __syncthreads();
+  auto stage_b = [&]() __attribute__((always_inline)) {
+    for (int v = threadIdx.x; v < 32 * NSB * vec_per_row; v += kProjWaves * 64) {
+      const int s = v / vec_per_row, kk = (v % vec_per_row) * 8;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (s < S_grp && kk < klen) val = *reinterpret_cast<const uint4 *>(hsrc + (size_t)s * tab.d + kk);
+      *reinterpret_cast<uint4 *>(Bs + s * ldb + kk) = val;
+    }
+    __syncthreads();
+  };
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hf = lane >> 5;
@@ -158,8 +160,9 @@ __global__ __launch_bounds__(WAVES * 64) void project_mfma_kernel(const SampleTa
   if (klen == tab.kslice) {          // full slice: straight-line loads
     u32x4_t w0[4], w1[4];            // two k-steps in flight
     const int klast = tab.kslice - 64;
-    fetch_w(w0, 0);
+    fetch_w(w0, 0);                  // the first W_q rows are on their way while the sampled states are staged
     fetch_w(w1, min(64, klast));
+    stage_b();
     for (int kk = 0; kk < tab.kslice; kk += 128) {
       stage_w(w0);
       fetch_w(w0, min(kk + 128, klast));             // (past the end a step is fetched again: no conditional load)
@@ -175,6 +178,7 @@ __global__ __launch_bounds__(WAVES * 64) void project_mfma_kernel(const SampleTa
       }
     }
   } else {                           // the last, shorter slice: guarded element-wise loads
+    stage_b();
     const int o = min(ob + col, tab.n_out - 1);
     const bf16_t *wrow = reinterpret_cast<const bf16_t *>(tab.it[it].w_q) + (size_t)o * tab.d + k0 + hf * 32;
     for (int kk = 0; kk < tab.kslice; kk += 64) {
