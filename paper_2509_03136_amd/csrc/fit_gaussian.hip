@@ -21,8 +21,7 @@ __global__ __launch_bounds__(kFitThreads) void moments_partial_kernel(const FitT
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int chunk = blockIdx.y;
-  int it = 0;
-  while (it + 1 < tab.n_items && chunk >= tab.it[it + 1].chunk0) ++it;
+  const int it = item_of_chunk(tab, chunk, 0);
   const FitItem I = tab.it[it];
   const int col = (blockIdx.x * 64 + lane) * NV;
   const bool active = col < tab.d;

@@ -17,6 +17,19 @@ constexpr size_t kLdsBytesPerCu = 160 * 1024;   // LDS of one gfx950 compute uni
 // Items per launch batch.  Tables are kernel arguments (<= 4 KiB), larger calls are split.
 constexpr int kMaxItems = 32;
 
+// The item a launch-wide chunk number falls into: the last item whose first chunk (`chunk0`, counted from `base`)
+// is not beyond it.  Items are in ascending chunk order; a bisection over the table in the kernel arguments.
+template <typename Table>
+__device__ __forceinline__ int item_of_chunk(const Table &tab, int chunk, int base) {
+  int lo = 0, hi = tab.n_items - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (chunk >= tab.it[mid].chunk0 - base) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
 typedef unsigned short bf16_t;   // storage only; arithmetic is fp32
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }

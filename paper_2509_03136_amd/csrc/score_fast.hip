@@ -1141,9 +1141,12 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
     const unsigned long long mykey = have ? M.key[lane] : 0ull;
     const uint32_t myw = have ? M.wgt[lane] : 0u;
     unsigned long long ahead = 0ull;       // fixed-point weight of the candidates ranked before mine
-    for (int j = 0; j < cnt; ++j) {
-      const unsigned long long kj = __shfl(mykey, j, 64);
-      const uint32_t wj = __shfl(myw, j, 64);
+    const uint32_t klo = (uint32_t)mykey, khi = (uint32_t)(mykey >> 32);
+    const int n = __builtin_amdgcn_readfirstlane(cnt);
+    for (int j = 0; j < n; ++j) {          // j is wave-uniform: lane reads through scalar registers, no LDS traffic
+      const unsigned long long kj = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)khi, j) << 32) |
+                                    (unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)klo, j);
+      const uint32_t wj = (uint32_t)__builtin_amdgcn_readlane((int)myw, j);
       if (kj > mykey) ahead += wj;
     }
     if (have && above + (double)ahead < target) {

@@ -27,12 +27,12 @@ constexpr int kMaxDevices = 64;
 void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, looked up once
 std::mutex g_scratch_mutex;
 
-// grid: one wave per chunk, 4 chunks per workgroup
+// grid: one workgroup of four waves per chunk; each wave ORs a quarter of the group's rows, wave 0 combines
 __global__ __launch_bounds__(256) void union_count_kernel(const UnionTable tab) {
+  __shared__ uint32_t part[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int chunk = blockIdx.x * 4 + wave;            // within this batch
-  int it = 0;
-  while (it + 1 < tab.n_items && chunk >= tab.it[it + 1].chunk0 - tab.it[0].chunk0) ++it;
+  const int chunk = blockIdx.x;                       // within this batch
+  const int it = item_of_chunk(tab, chunk, tab.it[0].chunk0);
   const UnionItem I = tab.it[it];
   const int local = chunk - (I.chunk0 - tab.it[0].chunk0);
   if (it == tab.n_items - 1 && local >= I.n_chunks * tab.n_kv_heads) return;
@@ -42,19 +42,27 @@ __global__ __launch_bounds__(256) void union_count_kernel(const UnionTable tab) 
   uint32_t acc = 0u;
   if (word < I.W) {
     const uint32_t *rm = tab.rowmask + I.rowmask_off + word;
-    // the S*G rows of the group, eight loads in flight at a time
+    // this wave's share of the S*G rows of the group, eight loads in flight at a time
     const int n_rows = tab.S * G;
-    for (int i0 = 0; i0 < n_rows; i0 += 8) {
+    const int per_wave = (n_rows + 3) / 4;
+    const int i_end = min(n_rows, (wave + 1) * per_wave);
+    for (int i0 = wave * per_wave; i0 < i_end; i0 += 8) {
       uint32_t v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const int i = min(i0 + u, n_rows - 1);          // the last row is simply read again
+        const int i = min(i0 + u, i_end - 1);           // the last row is simply read again
         const int s = i / G, g = i - s * G;
         v[u] = rm[(long long)(s * tab.n_q_heads + kvh * G + g) * I.W];
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc |= v[u];
     }
+  }
+  part[wave][lane] = acc;
+  __syncthreads();
+  if (wave != 0) return;
+  acc = part[0][lane] | part[1][lane] | part[2][lane] | part[3][lane];
+  if (word < I.W) {
     if (word == I.W - 1 && (I.L & 31)) acc &= (1u << (I.L & 31)) - 1u;   // never trust bits beyond L
     tab.union_mask[I.union_off + (long long)kvh * I.W + word] = acc;
   }
@@ -112,8 +120,7 @@ __global__ __launch_bounds__(1024) void scan_chunks_kernel(const int *chunk_coun
 template <typename T>
 __global__ __launch_bounds__(256) void gather_kernel(const UnionTable tab) {
   const int chunk = blockIdx.x;
-  int it = 0;
-  while (it + 1 < tab.n_items && chunk >= tab.it[it + 1].chunk0 - tab.it[0].chunk0) ++it;
+  const int it = item_of_chunk(tab, chunk, tab.it[0].chunk0);
   const UnionItem I = tab.it[it];
   const int local = chunk - (I.chunk0 - tab.it[0].chunk0);
   const int kvh = local / I.n_chunks, c = local - kvh * I.n_chunks;
@@ -287,7 +294,7 @@ gvote_status launch_union_compact(const gvote_shape *sh, const gvote_item *items
         batch_chunks += u.n_chunks * sh->n_kv_heads;
       }
       if (phase == 0) {
-        hipLaunchKernelGGL(union_count_kernel, dim3(ceil_div(batch_chunks, 4)), dim3(256), 0, st, tab);
+        hipLaunchKernelGGL(union_count_kernel, dim3(batch_chunks), dim3(256), 0, st, tab);
       } else if (sh->dtype == GVOTE_F32) {
         hipLaunchKernelGGL(gather_kernel<float>, dim3(batch_chunks), dim3(256), 0, st, tab);
       } else {
