@@ -457,10 +457,10 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(const FastTable ta
 
 // ------------------------------------------------------------------ per row: bin of the cut.  One wave per row.
 constexpr int kFindWaves = 4;
-// MANY: an item of the call has more than four chunks (a long single item has hundreds): the lanes share out the
-// chunks' maxima, and the loop over the histograms issues its loads unconditionally, four chunks at a time, so that
-// their latencies overlap (at the price of registers, which the usual few-chunk case would only lose occupancy to).
-template <bool MANY>
+// The lanes share out the chunks' maxima and window tops; the histograms are merged GROUP chunks at a time, every load
+// of a group issued before any is used, so that their latencies overlap (GROUP = 2 when no item of the call has more
+// than two chunks, the large-batch case, where registers cost occupancy; else 4).
+template <int GROUP>
 __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTable tab, int n_rows) {
   const int lane = threadIdx.x & 63;
   const int grow = blockIdx.x * kFindWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -474,19 +474,19 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
   float m = -INFINITY;
   int top = kTopUnset;
   bool gave_up = false;
-  for (int ch = MANY ? lane : 0; ch < I.n_chunks; ch += MANY ? 64 : 1) {
+  int tc_lane = kTopUnset;            // window top of chunk `lane`
+  for (int ch = lane; ch < I.n_chunks; ch += 64) {
     m = fmaxf(m, tab.part_max[(slot0 + ch) * tab.NQ + n]);
     const int tc = tab.part_top[(slot0 + ch) * tab.NQ + n];
+    if (ch < 64) tc_lane = tc;
     gave_up = gave_up || tc == kTopGaveUp;
     top = max(top, tc);
   }
-  if (MANY) {
-    for (int off = 32; off > 0; off >>= 1) {
-      m = fmaxf(m, __shfl_xor(m, off, 64));
-      top = max(top, __shfl_xor(top, off, 64));
-    }
-    gave_up = __any(gave_up);
+  for (int off = 32; off > 0; off >>= 1) {
+    m = fmaxf(m, __shfl_xor(m, off, 64));
+    top = max(top, __shfl_xor(top, off, 64));
   }
+  gave_up = __any(gave_up);
   RowInfo *info = tab.info + grow;
   if (gave_up) {      // a pass-1 workgroup of this row gave up: no histogram to trust, the exact selector redoes the row
     if (lane == 0) {
@@ -511,35 +511,39 @@ __global__ __launch_bounds__(kFindWaves * 64) void find_bin_kernel(const FastTab
 #pragma unroll
   for (int i = 0; i < BPL; ++i) acc[i] = 0ull;
   float tailpart = 0.f;    // this lane's share of the last global bin, relative to that bin's edge
-  // few chunks (large batches): one after the other, loads only where they are needed
-  for (int ch = 0; ch < (MANY ? 0 : I.n_chunks); ++ch) {
-    const int shift = top - tab.part_top[(slot0 + ch) * tab.NQ + n];
-    const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
+  // GROUP chunks at a time; the last group repeats its last chunk with weight zero
+  for (int ch0 = 0; ch0 < I.n_chunks; ch0 += GROUP) {
+    int shift[GROUP];
+    const uint32_t *hc[GROUP];
 #pragma unroll
-    for (int i = 0; i < BPL; ++i) {
-      const int j = lane + 64 * i;
-      const uint32_t u = hc[j];                       // chunk bin j
-      const int over = min(j + shift - (kBins - 1), 1 << 20);   // >= 0: it lands in or beyond the last global bin
-      if (over >= 0 && u) tailpart += topk ? (float)u : (float)u * __builtin_amdgcn_exp2f(-(float)over * kLog2ePerBin);
-      const int jl = j - shift;                        // chunk bin that lands in my global bin j
-      if (j < kBins - 1 && jl >= 0) acc[i] += hc[min(jl, kBins - 1)];
+    for (int u = 0; u < GROUP; ++u) {
+      const int ch = min(ch0 + u, I.n_chunks - 1);
+      // (the first 64 chunks' tops are still in the lanes that fetched them: no second, dependent load)
+      const int tc = ch < 64 ? __builtin_amdgcn_readlane(tc_lane, ch) : tab.part_top[(slot0 + ch) * tab.NQ + n];
+      shift[u] = top - tc;             // >= 0; tops are bounded, the difference fits
+      hc[u] = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
     }
-  }
-  // many chunks (a long single item): unconditional loads, four chunks at a time, so that their latencies overlap
-#pragma unroll 4
-  for (int ch = 0; ch < (MANY ? I.n_chunks : 0); ++ch) {
-    const int shift = top - tab.part_top[(slot0 + ch) * tab.NQ + n];      // >= 0; tops are bounded, the difference fits
-    const uint32_t *hc = tab.part_hist + ((slot0 + ch) * tab.NQ + n) * kBins;
+    uint32_t hu[GROUP][BPL], hv[GROUP][BPL];
 #pragma unroll
-    for (int i = 0; i < BPL; ++i) {
-      const int j = lane + 64 * i;
-      const uint32_t u = hc[j];                       // chunk bin j
-      const int over = min(j + shift - (kBins - 1), 1 << 20);   // >= 0: it lands in or beyond the last global bin
-      const float wt = topk ? (float)u : (float)u * __builtin_amdgcn_exp2f(-(float)over * kLog2ePerBin);
-      tailpart += over >= 0 ? wt : 0.f;
-      const int jl = j - shift;                        // chunk bin that lands in my global bin j
-      const uint32_t v = hc[min(max(jl, 0), kBins - 1)];   // (a valid bin whatever the workspace holds)
-      acc[i] += (j < kBins - 1 && jl >= 0) ? v : 0u;
+    for (int u = 0; u < GROUP; ++u) {
+#pragma unroll
+      for (int i = 0; i < BPL; ++i) {
+        const int j = lane + 64 * i;
+        hu[u][i] = hc[u][j];                                          // chunk bin j
+        hv[u][i] = hc[u][min(max(j - shift[u], 0), kBins - 1)];       // chunk bin that lands in my global bin j (a valid bin whatever the workspace holds)
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < GROUP; ++u) {
+      const bool live = ch0 + u < I.n_chunks;
+#pragma unroll
+      for (int i = 0; i < BPL; ++i) {
+        const int j = lane + 64 * i;
+        const int over = min(j + shift[u] - (kBins - 1), 1 << 20);   // >= 0: it lands in or beyond the last global bin
+        const float wt = (float)hu[u][i] * (topk ? 1.0f : __builtin_amdgcn_exp2f(-(float)over * kLog2ePerBin));
+        tailpart += (live && over >= 0) ? wt : 0.f;
+        acc[i] += (live && j < kBins - 1 && j - shift[u] >= 0) ? hv[u][i] : 0u;
+      }
     }
   }
   for (int off = 32; off > 0; off >>= 1) tailpart += __shfl_xor(tailpart, off, 64);
@@ -1201,10 +1205,10 @@ gvote_status launch_passes(const FastTable &tab, int grid_wg, int rows, bool top
   if (topk) hipLaunchKernelGGL((score_hist_kernel<DK, true, NT>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
   else hipLaunchKernelGGL((score_hist_kernel<DK, false, NT>), dim3(grid_wg), dim3(kThreads), 0, st, tab);
   GVOTE_CHECK_LAUNCH();
-  if (tab.sub_per_row > 4 * tab.emit_split * 2 * kWaves)      // (= the call's largest chunk count is above four)
-    hipLaunchKernelGGL(find_bin_kernel<true>, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
+  if (tab.sub_per_row > 2 * tab.emit_split * 2 * kWaves)      // (= the call's largest chunk count is above two)
+    hipLaunchKernelGGL(find_bin_kernel<4>, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
   else
-    hipLaunchKernelGGL(find_bin_kernel<false>, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
+    hipLaunchKernelGGL(find_bin_kernel<2>, dim3(ceil_div(rows, kFindWaves)), dim3(kFindWaves * 64), 0, st, tab, rows);
   GVOTE_CHECK_LAUNCH();
   for (int lvl = 0; lvl < kRefineLevels; ++lvl) {
     if (topk) hipLaunchKernelGGL((score_refine_kernel<DK, true, NT>), dim3(grid_wg), dim3(kThreads), 0, st, tab, lvl);
