@@ -1072,7 +1072,23 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   const int grow = blockIdx.x * kResolveWaves + wave;
   if (grow >= n_rows) return;
   RowInfo *info = tab.info + grow;
-  const int flag = info->flag;
+  if (SECOND) {                          // the second tier has nothing to do for nearly every row: look before fetching
+    const int f = info->flag;
+    if (!(f & 1) && f != 2) return;
+  }
+  // Everything that does not depend on the row's record is requested before the record is looked at: the record
+  // itself in one piece, the length of the overflow list and the lengths of the first 256 sub-lists.
+  const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
+  const FastItem I = tab.it[it];
+  const int n_sub = I.n_chunks * tab.emit_split * 2 * kWaves;
+  const int *ccnt = tab.cand_cnt + (size_t)grow * tab.sub_per_row;
+  const uint2 *clist = tab.cands + (size_t)grow * tab.sub_per_row * kSubCap;
+  int nn[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) nn[u] = 64 * u + lane < n_sub ? ccnt[64 * u + lane] : 0;
+  const int ovf_raw = tab.ovf_cnt[grow];
+  const RowInfo R = *info;
+  const int flag = R.flag;
   if (SECOND && (flag & 1)) {           // settled as "needs the exact selector": queue the row
     if (lane == 0) {
       tab.row_list[atomicAdd(tab.n_list, 1)] = grow;
@@ -1082,51 +1098,55 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
   }
   if (SECOND ? flag != 2 : flag != 0) return;
   ResolveLds<CAP> &M = lds[wave];
-  const int it = grow / tab.rows_per_item, r = grow - it * tab.rows_per_item;
-  const FastItem I = tab.it[it];
   // fixed-point scale: weights relative to the upper edge of the cut bin, 2^kFixBits each at most
-  const double edge = ldexp((double)(info->astar + 1) * (double)kLog2ePerBin, -info->shift);       // log2 units
+  const double edge = ldexp((double)(R.astar + 1) * (double)kLog2ePerBin, -R.shift);       // log2 units
   const float efix = (float)((double)kFixBits - edge);
   const bool topk = tab.mode == GVOTE_SELECT_TOPK;
-  const double unit = topk ? 1.0 : exp2((double)info->mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);
-  const double target = info->target * unit;
-  double above = info->above * unit;
+  const double unit = topk ? 1.0 : exp2((double)R.mdot * (double)tab.c2 - edge) * (double)(1 << kFixBits);
+  const double target = R.target * unit;
+  double above = R.above * unit;
+  auto put = [&](int dst, uint2 e) __attribute__((always_inline)) {
+    const float d = __uint_as_float(e.x);
+    M.key[dst] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
+    M.wgt[dst] = topk ? 1u : (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
+  };
+  // the row's shared overflow list: its first 64 entries are on their way while the sub-lists are gathered
+  const int n_ovf = max(0, min(ovf_raw, kOvfCap));
+  const uint2 ovf_first = lane < n_ovf ? tab.ovf[(size_t)grow * kOvfCap + lane] : make_uint2(0u, 0u);
 
-  // gather the sub-lists (order is irrelevant: keys are unique)
-  const int n_sub = I.n_chunks * tab.emit_split * 2 * kWaves;
+  // gather the sub-lists (order is irrelevant: keys are unique), 256 of them at a time: their counts are fetched
+  // together (those of the next 256 while these are worked on), then the first entry of each (most hold none or
+  // one), so that a row does not pay a memory round trip per step
   int cnt = 0;
-  for (int s0 = 0; s0 < n_sub; s0 += 64) {
-    const int sub = s0 + lane;
-    const int n = sub < n_sub ? tab.cand_cnt[(size_t)grow * tab.sub_per_row + sub] : 0;
-    int x = n;
-    for (int off = 1; off < 64; off <<= 1) {
-      const int y = __shfl_up(x, off, 64);
-      if (lane >= off) x += y;
-    }
-    const int dst0 = cnt + x - n;
-    const uint2 *src = tab.cands + ((size_t)grow * tab.sub_per_row + sub) * kSubCap;
-    for (int i = 0; i < n; ++i) {
-      if (dst0 + i < CAP) {
-        const uint2 e = src[i];
-        const float d = __uint_as_float(e.x);
-        M.key[dst0 + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-        M.wgt[dst0 + i] = topk ? 1u : (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
+  for (int s0 = 0; s0 < n_sub; s0 += 256) {
+    uint2 first[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      first[u] = nn[u] > 0 ? clist[(size_t)(s0 + 64 * u + lane) * kSubCap] : make_uint2(0u, 0u);
+    int nn_next[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) nn_next[u] = s0 + 256 + 64 * u + lane < n_sub ? ccnt[s0 + 256 + 64 * u + lane] : 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (s0 + 64 * u >= n_sub) break;
+      const int n = nn[u];
+      int x = n;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off, 64);
+        if (lane >= off) x += y;
       }
+      const int dst0 = cnt + x - n;
+      const uint2 *src = clist + (size_t)(s0 + 64 * u + lane) * kSubCap;
+      for (int i = 0; i < n; ++i)
+        if (dst0 + i < CAP) put(dst0 + i, i == 0 ? first[u] : src[i]);
+      cnt += __shfl(x, 63, 64);
     }
-    cnt += __shfl(x, 63, 64);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) nn[u] = nn_next[u];
   }
-  {   // the row's shared overflow list
-    const int n_ovf = min(tab.ovf_cnt[grow], kOvfCap);
-    for (int i = lane; i < n_ovf; i += 64) {
-      if (cnt + i < CAP) {
-        const uint2 e = tab.ovf[(size_t)grow * kOvfCap + i];
-        const float d = __uint_as_float(e.x);
-        M.key[cnt + i] = ((unsigned long long)ordered_bits(d) << 32) | (unsigned long long)(0xFFFFFFFFu - e.y);
-        M.wgt[cnt + i] = topk ? 1u : (uint32_t)__builtin_amdgcn_exp2f(fmaf(d, tab.c2, efix));
-      }
-    }
-    cnt += n_ovf;
-  }
+  for (int i = lane; i < n_ovf; i += 64)
+    if (cnt + i < CAP) put(cnt + i, i < 64 ? ovf_first : tab.ovf[(size_t)grow * kOvfCap + i]);
+  cnt += n_ovf;
   if (cnt > CAP) {
     if (lane == 0) {
       info->flag = (!SECOND && cnt <= kCandCap) ? 2 : 5;   // 5: more candidates than the resolver holds
@@ -1159,8 +1179,17 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
     }
     return;
   }
-  unsigned long long prefix = 0ull;
-  for (int pass = 0; pass < 8; ++pass) {
+  // The candidates share a bin, hence the leading bytes of their keys: the search starts at the first byte in which
+  // two of them differ, and ends as soon as the digit it picks holds a single key (that key is the last one needed).
+  unsigned long long diff = 0ull;
+  {
+    const unsigned long long k0 = M.key[0];
+    for (int i = lane; i < cnt; i += 64) diff |= M.key[i] ^ k0;
+    for (int off = 32; off > 0; off >>= 1) diff |= __shfl_xor(diff, off, 64);
+  }
+  const int first_pass = diff ? __clzll((long long)diff) >> 3 : 7;
+  unsigned long long prefix = first_pass ? M.key[0] >> (64 - 8 * first_pass) : 0ull;
+  for (int pass = first_pass; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
 #pragma unroll
     for (int i = 0; i < 4; ++i) { M.hist[lane * 4 + i] = 0u; M.hcnt[lane * 4 + i] = 0; }
@@ -1176,7 +1205,12 @@ __global__ __launch_bounds__((SECOND ? 1 : 4) * 64) void resolve_kernel(const Fa
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     const int pick = pick_digit_wave(M.hist, M.hcnt, above, target, lane);
     prefix = (prefix << 8) | (unsigned long long)(pick & 255);
+    const bool single = M.hcnt[pick & 255] == 1;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    if (single) {
+      prefix <<= shift;      // (the remaining bytes as zeros: the one key of the digit is not below that)
+      break;
+    }
   }
   for (int i = lane; i < cnt; i += 64) {
     if (M.key[i] >= prefix) {
