@@ -24,9 +24,10 @@ Pins (tests/test_oracle_pins.py, CPU only): Philox against the generator's
 published known-answer vectors; normals by distribution tests against SciPy's
 normal law; moments, RoPE, top-p by closed forms; top-p by brute-force subset
 enumeration; projection/scores by hand-built one-hot cases; union/compaction by
-set arithmetic on hand-written examples; decode attention against SciPy's softmax
-and closed forms (equal keys -> mean of V, a dominant key -> its V); overlap by
-its bounds and the full-set / complement identities.  `gvote_item` (the composition, i.e.
+set arithmetic on hand-written examples; decode attention against SciPy's softmax,
+closed forms (equal keys -> mean of V, a dominant key -> its V) and values worked out
+by hand (weights 1:3, the group map, the log-sum-exp); overlap by hand-worked values
+(weights 1:2:3:4 per head, shared KV head), its bounds and the full-set / complement identities.  `gvote_item` (the composition, i.e.
 end-to-end budgets on synthetic inputs) has no printed value in the paper to
 compare with: parity unpinned for its budgets beyond the invariants the tests
 state (union >= every row set, monotone in p and S, p -> 1 keeps all).

@@ -397,6 +397,37 @@ def test_attention_overlap_identities():
     assert np.all(O.attention_overlap(q, k, own) >= 0.9 - 1e-12)
 
 
+def test_consumer_side_hand_worked_values():
+    """Values worked out by hand (Eq. (1)-(2), Sec. 3.3): with d_k = 4 and q = (2, 0, 0, 0) a key (ln w, 0, 0, 0) has logit
+    ln w, i.e. attention weight w / sum(w)."""
+    ln = math.log
+    # decode attention over a packed cache of two heads with two rows each
+    q = np.array([[2.0, 0, 0, 0], [2.0, 0, 0, 0]])
+    k_out = np.array([[ln(1), 0, 0, 0], [ln(3), 0, 0, 0], [ln(2), 0, 0, 0], [ln(2), 0, 0, 0]])
+    v_out = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 0, 8.0, 0], [0, 0, 0, 4.0]])
+    out, lse = O.decode_attention(q, k_out, v_out, np.array([0, 2, 4]), 2)
+    assert np.allclose(out[0], [0.25, 0.75, 0, 0]) and np.allclose(out[1], [0, 0, 4.0, 2.0])
+    assert np.allclose(lse, [ln(4), ln(4)])
+    # one KV head shared by both query heads: the group map sends both to rows 0..3
+    out, lse = O.decode_attention(np.array([[2.0, 0, 0, 0], [4.0, 0, 0, 0]]), k_out, v_out, np.array([0, 4]), 1)
+    assert np.allclose(out[0], [1 / 8, 3 / 8, 2.0, 1.0]) and np.allclose(lse[0], ln(8))
+    assert np.allclose(out[1], [1 / 18, 9 / 18, 8 * 4 / 18, 4 * 4 / 18]) and np.allclose(lse[1], ln(18))   # weights w^2
+    # overlap: weights (1, 2, 3, 4) / 10 for head 0 on KV head 0, (4, 3, 2, 1) / 10 for head 1 on KV head 1
+    k = np.zeros((4, 2, 4))
+    k[:, 0, 0] = [ln(1), ln(2), ln(3), ln(4)]
+    k[:, 1, 0] = [ln(4), ln(3), ln(2), ln(1)]
+    rm = np.zeros((2, 2, 4), dtype=bool)
+    rm[0, 0, [1, 3]] = True          # sample 0, head 0: keys 1 and 3 -> 0.2 + 0.4
+    rm[0, 1, 0] = True               # sample 0, head 1: key 0 -> 0.4
+    rm[1, 0, 0] = True               # sample 1, head 0: key 0 -> 0.1
+    rm[1, 1, [2, 3]] = True          # sample 1, head 1: keys 2, 3 -> 0.3
+    ov = O.attention_overlap(q, k, rm)
+    assert np.allclose(ov, [[0.6, 0.4], [0.1, 0.3]])
+    # both query heads on one KV head, the second with twice the query: weights w^2 / 30
+    ov = O.attention_overlap(np.array([[2.0, 0, 0, 0], [4.0, 0, 0, 0]]), k[:, :1], rm)
+    assert np.allclose(ov, [[0.6, 1 / 30], [0.1, (9 + 16) / 30]])
+
+
 # ---------------------------------------------------------------- test infrastructure itself
 def test_band_sets_bracket_the_oracle_selection():
     import sys
